@@ -1,0 +1,219 @@
+"""Oracle for the planning half of MG-WFBP.  TEST INFRASTRUCTURE ONLY (see oracle/__init__.py).
+
+Everything is written in the paper's notation with 1-based layer numbers: layer 1 is the input
+side, layer L the output side; backpropagation visits L, L-1, ..., 1.  Internally lists carry an
+unused slot 0 so that `x[l]` reads like the paper's x^(l).  Public functions take and return
+0-based sequences in forward order (position i holds layer l = i + 1).
+
+All times are Python floats (IEEE binary64), one rounding per written operation, evaluated in the
+order the paper writes them.  Message sizes are exact Python integers (bytes).
+
+Readings taken where the paper leaves a choice:
+  * b multiplies BYTES (Eq. 10 defines M in bytes); Algorithm 1's `b x p[l]` is read with p[l]
+    expressed in bytes.
+  * tau_b^(L) = 0, as Algorithm 1 initialises it (Eq. 6 has t_f there; a constant shift).
+  * The merge test is the one Algorithm 1 spells out, `tau_b[l-1] + t_b[l-1] - tau_c[l] < a`,
+    evaluated left to right, strict; equality keeps the layer normal (Case 3 uses ">=").
+  * Layer 1 can never be merged (first property of a merged-gradient layer), so there are
+    2^(L-1) candidate plans, not 2^L.
+  * Inside a merge buffer tensors lie in arrival order (layer L-side first), densely (Sec. 5.3
+    sizes the buffer as the plain sum of the member sizes).
+
+Parity pins live in tests/test_oracle_plan.py (hand-evaluated timelines, closed forms for the
+all-normal and all-merged plans, the paper's 200 KB / 400 KB example, exhaustive search,
+limit cases, a group-level timeline simulation written independently of Eq. 7).
+The group counts the paper prints for its simulated clusters (Sec. 6.4) need backward-time traces
+that are not available: parity unpinned for those.
+"""
+from __future__ import annotations
+
+from typing import List, Sequence, Tuple
+
+NORMAL = 0   # l_n
+MERGED = 1   # l_m
+
+
+# ------------------------------------------------------------------------------------------
+# Eq. 10: all-reduce cost model
+# ------------------------------------------------------------------------------------------
+
+def allreduce_time(a: float, b: float, message_bytes: int) -> float:
+    """T_ar(M) = a + b x M  (Eq. 10)."""
+    return a + b * float(message_bytes)
+
+
+# ------------------------------------------------------------------------------------------
+# Eq. 6 / Eq. 7: the wait-free backpropagation timeline
+# ------------------------------------------------------------------------------------------
+
+def _one_based(seq: Sequence) -> list:
+    return [None] + list(seq)
+
+
+def backward_start_times(t_b1: list) -> list:
+    """tau_b^(l) for l = 1..L with tau_b^(L) = 0 (Eq. 6, Algorithm 1 initialisation)."""
+    L = len(t_b1) - 1
+    tau_b = [None] * (L + 1)
+    tau_b[L] = 0.0
+    for l in range(L - 1, 0, -1):
+        tau_b[l] = tau_b[l + 1] + t_b1[l + 1]
+    return tau_b
+
+
+def comm_start_times(t_c1: list, t_b1: list, tau_b1: list) -> list:
+    """tau_c^(l) for l = 1..L (Eq. 7; procedure CalculateCommStart of Algorithm 1).
+
+    Layer L may communicate once its own gradient exists; any lower layer needs both its own
+    gradient and the end of the communication scheduled just before it."""
+    L = len(t_b1) - 1
+    tau_c = [None] * (L + 1)
+    tau_c[L] = tau_b1[L] + t_b1[L]
+    for l in range(L - 1, 0, -1):
+        tau_c[l] = max(tau_c[l + 1] + t_c1[l + 1], tau_b1[l] + t_b1[l])
+    return tau_c
+
+
+# ------------------------------------------------------------------------------------------
+# Eq. 8 with the merge properties Eq. 12-14: iteration time of a given plan
+# ------------------------------------------------------------------------------------------
+
+def iteration_time(merged: Sequence[int], size_bytes: Sequence[int], t_backward: Sequence[float],
+                   a: float, b: float) -> float:
+    """t_iter - t_f for the plan `merged` (0-based, merged[i] = 1 iff layer i+1 is merged into i).
+
+    A merged layer has no communication of its own (Eq. 12), hands its bytes to the layer below
+    (Eq. 13), and the layer below may start as soon as both are ready (Eq. 14, which is Eq. 7 with
+    t_c^(l) = 0).  The iteration ends when layer 1's message ends (Eq. 8)."""
+    L = len(size_bytes)
+    if L == 0:
+        return 0.0
+    if merged[0]:
+        raise ValueError("layer 1 cannot be a merged-gradient layer")
+    m = _one_based(merged)
+    p = _one_based(int(x) for x in size_bytes)
+    t_b = _one_based(float(x) for x in t_backward)
+    for l in range(L, 1, -1):
+        if m[l] == MERGED:
+            p[l - 1] = p[l - 1] + p[l]
+    t_c = [None] * (L + 1)
+    for l in range(1, L + 1):
+        t_c[l] = 0.0 if m[l] == MERGED else allreduce_time(a, b, p[l])
+    tau_b = backward_start_times(t_b)
+    tau_c = comm_start_times(t_c, t_b, tau_b)
+    return tau_c[1] + t_c[1]
+
+
+def wfbp_time(size_bytes, t_backward, a, b) -> float:
+    """Every layer normal: plain wait-free backpropagation."""
+    return iteration_time([NORMAL] * len(size_bytes), size_bytes, t_backward, a, b)
+
+
+def single_layer_time(size_bytes, t_backward, a, b) -> float:
+    """Layers L..2 all merged: one message after the whole backward pass (single-layer S-SGD, Eq. 9)."""
+    L = len(size_bytes)
+    return iteration_time([NORMAL] + [MERGED] * (L - 1), size_bytes, t_backward, a, b)
+
+
+# ------------------------------------------------------------------------------------------
+# Algorithm 1
+# ------------------------------------------------------------------------------------------
+
+def plan_algorithm1(size_bytes: Sequence[int], t_backward: Sequence[float], a: float, b: float
+                    ) -> List[int]:
+    """Algorithm 1, with the full re-evaluation of tau_c after every merge (O(L^2)).
+
+    Returns merged[0..L-1]; merged[0] is always 0."""
+    L = len(size_bytes)
+    if L == 0:
+        return []
+    p = _one_based(int(x) for x in size_bytes)
+    t_b = _one_based(float(x) for x in t_backward)
+    m = [None] + [NORMAL] * L
+    t_c = [None] * (L + 1)
+    for l in range(1, L + 1):
+        t_c[l] = allreduce_time(a, b, p[l])
+    tau_b = backward_start_times(t_b)
+    tau_c = comm_start_times(t_c, t_b, tau_b)
+    for l in range(L, 1, -1):
+        if tau_b[l - 1] + t_b[l - 1] - tau_c[l] < a:
+            # procedure Merge: layer l gives up its message and its bytes to layer l-1
+            t_c[l] = 0.0
+            p[l - 1] = p[l - 1] + p[l]
+            t_c[l - 1] = allreduce_time(a, b, p[l - 1])
+            tau_c = comm_start_times(t_c, t_b, tau_b)
+            m[l] = MERGED
+    return m[1:]
+
+
+def merge_rule_holds(l: int, tau_b1: list, t_b1: list, tau_c1: list, a: float) -> bool:
+    """Lemma 1 / Theorem 1's layer-type rule in its printed form: tau_b^(l-1)+t_b^(l-1) < tau_c^(l)+a."""
+    return tau_b1[l - 1] + t_b1[l - 1] < tau_c1[l] + a
+
+
+# ------------------------------------------------------------------------------------------
+# exhaustive search over the 2^(L-1) plans
+# ------------------------------------------------------------------------------------------
+
+def all_plans(L: int):
+    """Every plan with layer 1 normal, as 0-based flag lists."""
+    if L == 0:
+        return
+    for code in range(1 << (L - 1)):
+        yield [NORMAL] + [(code >> (i - 1)) & 1 for i in range(1, L)]
+
+
+def bruteforce_best(size_bytes, t_backward, a, b) -> Tuple[float, List[int]]:
+    """Minimum iteration time over all plans, and one plan attaining it (first in enumeration order)."""
+    L = len(size_bytes)
+    if L > 20:
+        raise ValueError("exhaustive search is meant for small L")
+    best_t = None
+    best_m = None
+    for m in all_plans(L):
+        t = iteration_time(m, size_bytes, t_backward, a, b)
+        if best_t is None or t < best_t:
+            best_t, best_m = t, m
+    return best_t, best_m
+
+
+# ------------------------------------------------------------------------------------------
+# Algorithm 2 (communication handler): which layers travel together; Sec. 5.3: buffer layout
+# ------------------------------------------------------------------------------------------
+
+def groups_in_arrival_order(merged: Sequence[int]) -> List[List[int]]:
+    """Replay the communication handler: layers are pushed L, L-1, ..., 1 into a layer buffer and the
+    buffer is all-reduced and cleared whenever the pushed layer is normal.
+
+    Returns groups of 0-based tensor indices, first-communicated group first; inside a group the
+    indices are in arrival order (descending)."""
+    L = len(merged)
+    groups: List[List[int]] = []
+    lb: List[int] = []
+    for l in range(L, 0, -1):
+        lb.append(l - 1)
+        if merged[l - 1] == NORMAL:
+            groups.append(lb)
+            lb = []
+    if lb:
+        raise ValueError("layer 1 must be normal")
+    return groups
+
+
+def merge_layout(n_elems: Sequence[int], merged: Sequence[int]):
+    """Element layout of the pre-allocated merge buffers (Sec. 5.3).
+
+    Returns (tensor_group[L], tensor_off[L], group_elems[G]): tensor i lives in buffer
+    tensor_group[i] at element offset tensor_off[i]; a buffer holds exactly the sum of its members'
+    elements, members in arrival order, no padding."""
+    L = len(n_elems)
+    tensor_group = [None] * L
+    tensor_off = [None] * L
+    group_elems = []
+    for k, members in enumerate(groups_in_arrival_order(merged)):
+        fill = 0
+        for i in members:
+            tensor_group[i] = k
+            tensor_off[i] = fill
+            fill += int(n_elems[i])
+        group_elems.append(fill)
+    return tensor_group, tensor_off, group_elems
