@@ -1,0 +1,211 @@
+/*
+ * mgwfbp.h -- C ABI of the MI355X (gfx950) merged-gradient hot path of MG-WFBP
+ *             (merged-gradient wait-free backpropagation).
+ *
+ * The library does two things:
+ *   1. HOST: decide which layers' gradients travel together (Algorithm 1), evaluate the
+ *      wait-free-backpropagation timeline of any such plan (Eq. 6-8 with the merged-layer
+ *      properties Eq. 12-14), and derive the merge-buffer layout (Sec. 5.3, Algorithm 2).
+ *   2. DEVICE: for one group or for all groups, on one GPU and one HIP stream,
+ *        pack           copy many per-layer gradient tensors of P workers into P contiguous
+ *                       merge buffers                                            (Sec. 5.3)
+ *        reduce         the per-GPU arithmetic of the all-reduce: sum the P merge buffers in
+ *                       worker order 0..P-1 and scale by 1/P                      (Eq. 2)
+ *        unpack_update  read the averaged gradient back out of the buffer and apply
+ *                       v <- mu*v + g ; w <- w - eta*v to the per-layer tensors   (Eq. 2,
+ *                       Algorithm 2 line 15; the momentum buffer is an addition of this library)
+ *      plus two fused forms that produce bit-identical results with less memory traffic.
+ *
+ * Conventions
+ *   - Tensor index i = 0..L-1 is the paper's layer l = i+1 (forward order).  Gradients become
+ *     ready in the order L-1, L-2, ..., 0 ("arrival order").
+ *   - merged[i] = 1 means layer i+1 is a merged-gradient layer: it sends nothing by itself and
+ *     its gradient is communicated together with tensor i-1.  merged[0] is always 0.
+ *   - A group is a maximal run hi >= ... >= lo with merged[i] = 1 for lo < i <= hi and
+ *     merged[lo] = 0.  Groups are numbered in arrival order: group 0 contains tensor L-1.
+ *   - Inside a group's slice of the merge buffer the tensors lie densely in arrival order
+ *     (tensor hi at element offset 0); the slice holds exactly the sum of its members' elements.
+ *   - All groups live in one "arena" per worker: group k's slice starts at element group_base[k],
+ *     which is a multiple of the library's tile size.  Elements between the end of one slice and
+ *     the next base are padding that no call reads or writes.
+ *   - Times are seconds (double).  Message sizes are bytes.  a and b are the startup time and the
+ *     per-byte time of the all-reduce cost model T(M) = a + b*M (Eq. 10).
+ *   - "device array" = memory readable by the GPU; "host array" = ordinary host memory.
+ *     The caller owns every buffer it passes in; the context owns only its own tables.
+ *   - Device entry points enqueue work on `hip_stream` (a hipStream_t passed as void*; NULL is
+ *     the default stream) and return without waiting for it.  They allocate nothing.
+ *   - Arithmetic is binary32 with one rounding per operation (no fused multiply-add):
+ *       r = ((..((g_0 + g_1) + g_2)..) + g_{P-1}) * (1.0f / P)
+ *       t1 = mu * v ; v' = t1 + r ; t2 = eta * v' ; w' = w - t2
+ *     bfloat16 gradients are widened exactly to binary32 before the first addition.
+ *   - Every function returns MGWFBP_OK (0) or a negative mgwfbp_status.  Nothing throws or aborts.
+ *     A failed call has enqueued nothing.
+ */
+#ifndef MGWFBP_H
+#define MGWFBP_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum mgwfbp_status {
+    MGWFBP_OK = 0,
+    MGWFBP_EINVAL = -1, /* null pointer, size or index out of range, non-finite or negative time */
+    MGWFBP_ENOMEM = -2, /* host or device allocation failed                                       */
+    MGWFBP_EHIP = -3    /* a HIP runtime call failed; see mgwfbp_last_hip_error()                 */
+} mgwfbp_status;
+
+typedef enum mgwfbp_dtype {
+    MGWFBP_F32 = 0, /* gradients are binary32, 4 bytes per element            */
+    MGWFBP_BF16 = 1 /* gradients are bfloat16 bit patterns, 2 bytes per element (Sec. 5.3:
+                       BytesPerElement = 2 for half-precision training)         */
+} mgwfbp_dtype;
+
+typedef struct mgwfbp_ctx mgwfbp_ctx; /* opaque; host + device copies of the group/offset tables */
+
+/* ---------------------------------------------------------------------------------------------
+ * Host: planning
+ * ------------------------------------------------------------------------------------------- */
+
+/* Algorithm 1 ("find optimal m").  For l = L..2 layer l becomes a merged-gradient layer iff
+ *     tau_b[l-1] + t_b[l-1] - tau_c[l] < a          (evaluated left to right, strict)
+ * where tau_b follows Eq. 6 with tau_b[L] = 0 and tau_c follows Eq. 7 under the merges decided so
+ * far; a merge moves the layer's bytes to layer l-1 and recomputes that layer's message time
+ * a + b*bytes.  The result equals the O(L^2) formulation of the paper bit for bit; this
+ * implementation updates tau_c incrementally and runs in O(L).
+ *
+ *   size_bytes    host [L]  gradient bytes of each tensor (may be 0)
+ *   t_backward_s  host [L]  backward time of each tensor, seconds, finite and >= 0
+ *   a_s, b_s_per_byte       cost model, finite and >= 0
+ *   merged_out    host [L]  out: 0 = normal layer, 1 = merged-gradient layer
+ *   group_first_out host [L+1] or NULL  out: group_first[k] = highest tensor index of group k,
+ *                           group_first[G] = -1
+ *   n_groups_out  host [1] or NULL      out: G
+ * L = 0 is accepted (G = 0).  Errors: MGWFBP_EINVAL. */
+int mgwfbp_plan(const uint64_t* size_bytes, const double* t_backward_s, int32_t L,
+                double a_s, double b_s_per_byte,
+                uint8_t* merged_out, int32_t* group_first_out, int32_t* n_groups_out);
+
+/* Iteration time minus forward time, t_iter - t_f, of an arbitrary plan: Eq. 8 evaluated on the
+ * timeline of Eq. 6-7 after applying Eq. 12 (no message for a merged layer), Eq. 13 (bytes move
+ * down) and Eq. 14 (start of the lower layer).  merged[0] must be 0.  Result in *t_iter_out. */
+int mgwfbp_eval(const uint8_t* merged, const uint64_t* size_bytes, const double* t_backward_s,
+                int32_t L, double a_s, double b_s_per_byte, double* t_iter_out);
+
+/* ---------------------------------------------------------------------------------------------
+ * Host: context = group/offset table for one (tensor sizes, plan, P, dtype), uploaded once
+ * ------------------------------------------------------------------------------------------- */
+
+/* Builds the layout described under "Conventions" and copies the tables that drive the kernels to
+ * the current HIP device (synchronous; this is the only allocating call besides destroy).
+ *   n_elems host [L]  element count of each tensor (0 allowed: such a tensor is skipped)
+ *   merged  host [L]  plan, e.g. from mgwfbp_plan
+ *   P       number of workers whose gradients are held on this GPU, 1..64
+ *   grad_dtype        mgwfbp_dtype of the gradient tensors and merge buffers
+ * Errors: MGWFBP_EINVAL, MGWFBP_ENOMEM, MGWFBP_EHIP. */
+int mgwfbp_ctx_create(mgwfbp_ctx** ctx_out, const uint64_t* n_elems, int32_t L,
+                      const uint8_t* merged, int32_t P, int32_t grad_dtype);
+
+/* Same tables, host copies only: needs no GPU and touches none.  Such a context answers the
+ * inspection calls below; every device entry point rejects it with MGWFBP_EINVAL. */
+int mgwfbp_ctx_create_host(mgwfbp_ctx** ctx_out, const uint64_t* n_elems, int32_t L,
+                           const uint8_t* merged, int32_t P, int32_t grad_dtype);
+
+void mgwfbp_ctx_destroy(mgwfbp_ctx* ctx); /* frees the tables; NULL is ignored */
+
+/* Sizes a caller needs before allocating: any out pointer may be NULL.
+ *   arena_elems  elements each merge buffer (and the reduced buffer) must hold
+ *   tile_elems   granule of the arena that one workgroup processes; group bases are multiples */
+int mgwfbp_ctx_dims(const mgwfbp_ctx* ctx, int32_t* L, int32_t* n_groups, int32_t* P,
+                    int32_t* grad_dtype, uint64_t* arena_elems, int32_t* tile_elems,
+                    int32_t* n_tiles);
+
+/* The layout, for inspection and tests.  Any out pointer may be NULL.
+ *   tensor_off   host [L]  element offset of tensor i inside its group's slice (Sec. 5.3: dense,
+ *                          arrival order)
+ *   tensor_group host [L]  group number of tensor i
+ *   group_base   host [G]  first arena element of group k
+ *   group_elems  host [G]  elements in group k (sum of its members) */
+int mgwfbp_ctx_layout(const mgwfbp_ctx* ctx, uint64_t* tensor_off, int32_t* tensor_group,
+                      uint64_t* group_base, uint64_t* group_elems);
+
+/* The tables the kernels walk, for tests of the host logic.  Any out pointer may be NULL.
+ * A "segment" is one non-empty tensor's stretch of the arena; segments are numbered in arena order.
+ *   n_segments     host [1]    S
+ *   tiles_out      host [n_tiles] records of 32 bytes: int64 first_start (arena start of the tile's
+ *                  first segment minus the tile's own start, <= 0), int32 first_end (tile-local end
+ *                  of that segment), int32 seg0 (its number), int32 nseg (segments intersecting the
+ *                  tile), int32 valid (leading elements of the tile inside the group), int32 layer0
+ *                  (tensor index of seg0), int32 reserved
+ *   seg_off_out    host [S+1]  arena element where each segment starts; [S] = arena_elems
+ *   seg_n_out      host [S]    elements of each segment, saturated at 2^32-1
+ *   seg_layer_out  host [S]    tensor index of each segment
+ *   group_tile_out host [G+1]  first tile of each group; [G] = n_tiles */
+int mgwfbp_ctx_tables(const mgwfbp_ctx* ctx, int32_t* n_segments, void* tiles_out,
+                      uint64_t* seg_off_out, uint32_t* seg_n_out, int32_t* seg_layer_out,
+                      int32_t* group_tile_out);
+
+/* Launch shape.  blocks_per_cu <= 0 restores the default; the grid is
+ * min(tiles of the call, compute units * blocks_per_cu) workgroups of 256 lanes, each striding
+ * over tiles.  xcd_contiguous != 0 renumbers workgroups so that each of the 8 accelerator dies
+ * walks one contiguous eighth of the tile range instead of every eighth tile. */
+int mgwfbp_ctx_set_launch(mgwfbp_ctx* ctx, int32_t blocks_per_cu, int32_t xcd_contiguous);
+
+/* ---------------------------------------------------------------------------------------------
+ * Device: the pipeline.  `group` is a group number 0..G-1, or -1 for every group in one launch.
+ *
+ * Pointer tables are DEVICE arrays of device pointers:
+ *   d_grad_ptrs  [P*L]  d_grad_ptrs[w*L + i] -> gradient tensor i of worker w, n_elems[i] elements
+ *                       of the context's dtype, element-aligned (16-byte alignment is faster)
+ *   d_merge_bufs [P]    d_merge_bufs[w] -> worker w's merge arena, arena_elems elements of the
+ *                       context's dtype, 16-byte aligned
+ *   d_w_ptrs, d_v_ptrs [L]  -> binary32 weight / momentum tensor i, n_elems[i] elements, 4-byte aligned
+ *   d_reduced           binary32 arena of arena_elems elements, 16-byte aligned
+ * Entries of zero-element tensors are never dereferenced.  Buffers of different roles must not
+ * overlap.  Calls on the same stream execute in order; calls for different groups touch disjoint
+ * elements and may run on different streams.
+ * Errors: MGWFBP_EINVAL (null argument, group out of range), MGWFBP_EHIP (launch failed).
+ * ------------------------------------------------------------------------------------------- */
+
+/* Sec. 5.3: copy the member gradients of `group`, for all P workers, into the merge arenas. */
+int mgwfbp_pack(mgwfbp_ctx* ctx, int32_t group, const void* const* d_grad_ptrs,
+                void* const* d_merge_bufs, void* hip_stream);
+
+/* Eq. 2, aggregation part: d_reduced[j] = (sum over w in order of merge[w][j]) * (1/P) for every
+ * element j of the group's slice. */
+int mgwfbp_reduce(mgwfbp_ctx* ctx, int32_t group, const void* const* d_merge_bufs,
+                  float* d_reduced, void* hip_stream);
+
+/* Eq. 2, update part (Algorithm 2 line 15) with momentum: for every member tensor i and element e,
+ * g = d_reduced[group_base + tensor_off[i] + e]; v_i[e] <- mu*v_i[e] + g; w_i[e] <- w_i[e] - lr*v_i[e]. */
+int mgwfbp_unpack_update(mgwfbp_ctx* ctx, int32_t group, const float* d_reduced,
+                         float* const* d_w_ptrs, float* const* d_v_ptrs,
+                         float lr, float momentum, void* hip_stream);
+
+/* reduce + unpack_update in one pass: reads the P merge slices, writes only w and v.
+ * Same bits as mgwfbp_reduce followed by mgwfbp_unpack_update. */
+int mgwfbp_reduce_update(mgwfbp_ctx* ctx, int32_t group, const void* const* d_merge_bufs,
+                         float* const* d_w_ptrs, float* const* d_v_ptrs,
+                         float lr, float momentum, void* hip_stream);
+
+/* pack + reduce + unpack_update in one pass: reads the per-layer gradients once, fills the merge
+ * arenas (the buffers an all-reduce would transmit), optionally writes the averaged gradient to
+ * d_reduced (NULL to skip), and updates w and v.  Same bits in every output as the three separate
+ * calls. */
+int mgwfbp_group_pipeline(mgwfbp_ctx* ctx, int32_t group, const void* const* d_grad_ptrs,
+                          void* const* d_merge_bufs, float* d_reduced,
+                          float* const* d_w_ptrs, float* const* d_v_ptrs,
+                          float lr, float momentum, void* hip_stream);
+
+/* ---------------------------------------------------------------------------------------------
+ * Diagnostics
+ * ------------------------------------------------------------------------------------------- */
+int mgwfbp_last_hip_error(void);      /* hipError_t of the last failed HIP call on this thread, 0 if none */
+const char* mgwfbp_version(void);     /* static string */
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MGWFBP_H */

@@ -1,0 +1,8 @@
+"""MI355X-native merged-gradient hot path of MG-WFBP: thin ctypes binding over libmgwfbp.so.
+
+Every step (plan, layout, pack, reduce, unpack + update) runs inside the C-ABI library; this package
+only marshals arguments.  Importing it does not load the library; the first call does, and fails
+loudly if the library has not been built (run `python -m paper_1912_09268_amd.build`)."""
+from .binding import (  # noqa: F401
+    BF16, F32, Context, MgwfbpError, eval_plan, lib, library_path, plan,
+)

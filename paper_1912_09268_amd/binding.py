@@ -1,0 +1,213 @@
+"""ctypes binding with the same names as the C ABI declared in include/mgwfbp.h.
+
+Argument marshalling only.  Device buffers are passed as integer addresses (e.g. torch's
+`tensor.data_ptr()`), streams as integer handles (e.g. `torch.cuda.current_stream().cuda_stream`)."""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Optional, Sequence, Tuple
+
+import numpy as np
+
+F32 = 0
+BF16 = 1
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB: Optional[C.CDLL] = None
+
+_STATUS = {0: "MGWFBP_OK", -1: "MGWFBP_EINVAL", -2: "MGWFBP_ENOMEM", -3: "MGWFBP_EHIP"}
+
+
+class MgwfbpError(RuntimeError):
+    def __init__(self, fn: str, status: int, hip_error: int = 0):
+        self.status = status
+        self.hip_error = hip_error
+        extra = f" (hipError_t {hip_error})" if status == -3 else ""
+        super().__init__(f"{fn} failed: {_STATUS.get(status, status)}{extra}")
+
+
+def library_path() -> str:
+    return os.environ.get("MGWFBP_LIBRARY", os.path.join(_HERE, "libmgwfbp.so"))
+
+
+_u64p = C.POINTER(C.c_uint64)
+_i32p = C.POINTER(C.c_int32)
+_u32p = C.POINTER(C.c_uint32)
+_u8p = C.POINTER(C.c_uint8)
+_f64p = C.POINTER(C.c_double)
+_vp = C.c_void_p
+
+_SIGNATURES = {
+    "mgwfbp_plan": (C.c_int, [_u64p, _f64p, C.c_int32, C.c_double, C.c_double, _u8p, _i32p, _i32p]),
+    "mgwfbp_eval": (C.c_int, [_u8p, _u64p, _f64p, C.c_int32, C.c_double, C.c_double, _f64p]),
+    "mgwfbp_ctx_create": (C.c_int, [C.POINTER(_vp), _u64p, C.c_int32, _u8p, C.c_int32, C.c_int32]),
+    "mgwfbp_ctx_create_host": (C.c_int, [C.POINTER(_vp), _u64p, C.c_int32, _u8p, C.c_int32, C.c_int32]),
+    "mgwfbp_ctx_destroy": (None, [_vp]),
+    "mgwfbp_ctx_dims": (C.c_int, [_vp, _i32p, _i32p, _i32p, _i32p, _u64p, _i32p, _i32p]),
+    "mgwfbp_ctx_layout": (C.c_int, [_vp, _u64p, _i32p, _u64p, _u64p]),
+    "mgwfbp_ctx_tables": (C.c_int, [_vp, _i32p, _vp, _u64p, _u32p, _i32p, _i32p]),
+    "mgwfbp_ctx_set_launch": (C.c_int, [_vp, C.c_int32, C.c_int32]),
+    "mgwfbp_pack": (C.c_int, [_vp, C.c_int32, _vp, _vp, _vp]),
+    "mgwfbp_reduce": (C.c_int, [_vp, C.c_int32, _vp, _vp, _vp]),
+    "mgwfbp_unpack_update": (C.c_int, [_vp, C.c_int32, _vp, _vp, _vp, C.c_float, C.c_float, _vp]),
+    "mgwfbp_reduce_update": (C.c_int, [_vp, C.c_int32, _vp, _vp, _vp, C.c_float, C.c_float, _vp]),
+    "mgwfbp_group_pipeline": (C.c_int, [_vp, C.c_int32, _vp, _vp, _vp, _vp, _vp, C.c_float, C.c_float, _vp]),
+    "mgwfbp_last_hip_error": (C.c_int, []),
+    "mgwfbp_version": (C.c_char_p, []),
+}
+
+
+def lib() -> C.CDLL:
+    """The loaded library.  Raises if it is missing: there is no fallback path."""
+    global _LIB
+    if _LIB is None:
+        path = library_path()
+        if not os.path.exists(path):
+            raise MgwfbpError(f"load {path} (not built; run `python -m paper_1912_09268_amd.build`)", -1)
+        handle = C.CDLL(path)
+        for name, (res, args) in _SIGNATURES.items():
+            fn = getattr(handle, name)
+            fn.restype = res
+            fn.argtypes = args
+        _LIB = handle
+    return _LIB
+
+
+def _check(fn: str, status: int) -> None:
+    if status != 0:
+        raise MgwfbpError(fn, status, lib().mgwfbp_last_hip_error())
+
+
+def _arr(x, dtype) -> np.ndarray:
+    return np.ascontiguousarray(np.asarray(x, dtype=dtype))
+
+
+def _ptr(a: Optional[np.ndarray], ctype):
+    return None if a is None else a.ctypes.data_as(ctype)
+
+
+# --------------------------------------------------------------------------------------------
+# host: planning
+# --------------------------------------------------------------------------------------------
+
+def plan(size_bytes: Sequence[int], t_backward_s: Sequence[float], a_s: float, b_s_per_byte: float
+         ) -> Tuple[np.ndarray, np.ndarray]:
+    """mgwfbp_plan.  Returns (merged[L] uint8, group_first[G] int32)."""
+    sz = _arr(size_bytes, np.uint64)
+    tb = _arr(t_backward_s, np.float64)
+    L = int(sz.shape[0])
+    if tb.shape[0] != L:
+        raise ValueError("size_bytes and t_backward_s differ in length")
+    merged = np.zeros(L, np.uint8)
+    first = np.zeros(L + 1, np.int32)
+    G = C.c_int32(0)
+    _check("mgwfbp_plan", lib().mgwfbp_plan(_ptr(sz, _u64p), _ptr(tb, _f64p), L, float(a_s), float(b_s_per_byte),
+                                            _ptr(merged, _u8p), _ptr(first, _i32p), C.byref(G)))
+    return merged, first[:G.value].copy()
+
+
+def eval_plan(merged: Sequence[int], size_bytes: Sequence[int], t_backward_s: Sequence[float],
+              a_s: float, b_s_per_byte: float) -> float:
+    """mgwfbp_eval: t_iter - t_f of a plan."""
+    m = _arr(merged, np.uint8)
+    sz = _arr(size_bytes, np.uint64)
+    tb = _arr(t_backward_s, np.float64)
+    out = C.c_double(0.0)
+    _check("mgwfbp_eval", lib().mgwfbp_eval(_ptr(m, _u8p), _ptr(sz, _u64p), _ptr(tb, _f64p), int(sz.shape[0]),
+                                            float(a_s), float(b_s_per_byte), C.byref(out)))
+    return out.value
+
+
+# --------------------------------------------------------------------------------------------
+# context + device calls
+# --------------------------------------------------------------------------------------------
+
+TILE_HDR_DTYPE = np.dtype([("first_start", np.int64), ("first_end", np.int32), ("seg0", np.int32),
+                           ("nseg", np.int32), ("valid", np.int32), ("layer0", np.int32),
+                           ("reserved", np.int32)])
+
+
+class Context:
+    """Owns one mgwfbp_ctx.  `host_only=True` builds the tables without touching a GPU (device calls
+    on such a context are rejected by the library)."""
+
+    def __init__(self, n_elems: Sequence[int], merged: Sequence[int], P: int, grad_dtype: int = F32,
+                 host_only: bool = False):
+        self._h = _vp(None)
+        ne = _arr(n_elems, np.uint64)
+        m = _arr(merged, np.uint8)
+        if ne.shape[0] != m.shape[0]:
+            raise ValueError("n_elems and merged differ in length")
+        fn = "mgwfbp_ctx_create_host" if host_only else "mgwfbp_ctx_create"
+        _check(fn, getattr(lib(), fn)(C.byref(self._h), _ptr(ne, _u64p), int(ne.shape[0]), _ptr(m, _u8p),
+                                      int(P), int(grad_dtype)))
+        L, G, Pq, dt, tile, nt = (C.c_int32() for _ in range(6))
+        arena = C.c_uint64()
+        _check("mgwfbp_ctx_dims", lib().mgwfbp_ctx_dims(self._h, C.byref(L), C.byref(G), C.byref(Pq), C.byref(dt),
+                                                        C.byref(arena), C.byref(tile), C.byref(nt)))
+        self.L, self.n_groups, self.P, self.grad_dtype = L.value, G.value, Pq.value, dt.value
+        self.arena_elems, self.tile_elems, self.n_tiles = arena.value, tile.value, nt.value
+
+    def close(self) -> None:
+        if self._h:
+            lib().mgwfbp_ctx_destroy(self._h)
+            self._h = _vp(None)
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    # ---- inspection -------------------------------------------------------------------
+    def layout(self):
+        """mgwfbp_ctx_layout -> (tensor_off[L], tensor_group[L], group_base[G], group_elems[G])."""
+        off = np.zeros(self.L, np.uint64)
+        grp = np.zeros(self.L, np.int32)
+        base = np.zeros(self.n_groups, np.uint64)
+        ge = np.zeros(self.n_groups, np.uint64)
+        _check("mgwfbp_ctx_layout", lib().mgwfbp_ctx_layout(self._h, _ptr(off, _u64p), _ptr(grp, _i32p),
+                                                            _ptr(base, _u64p), _ptr(ge, _u64p)))
+        return off, grp, base, ge
+
+    def tables(self):
+        """mgwfbp_ctx_tables -> dict of the tile / segment tables that drive the kernels."""
+        S = C.c_int32()
+        _check("mgwfbp_ctx_tables", lib().mgwfbp_ctx_tables(self._h, C.byref(S), None, None, None, None, None))
+        tiles = np.zeros(self.n_tiles, TILE_HDR_DTYPE)
+        seg_off = np.zeros(S.value + 1, np.uint64)
+        seg_n = np.zeros(S.value, np.uint32)
+        seg_layer = np.zeros(S.value, np.int32)
+        group_tile = np.zeros(self.n_groups + 1, np.int32)
+        _check("mgwfbp_ctx_tables", lib().mgwfbp_ctx_tables(
+            self._h, C.byref(S), tiles.ctypes.data_as(_vp), _ptr(seg_off, _u64p), _ptr(seg_n, _u32p),
+            _ptr(seg_layer, _i32p), _ptr(group_tile, _i32p)))
+        return {"tiles": tiles, "seg_off": seg_off, "seg_n": seg_n, "seg_layer": seg_layer,
+                "group_tile": group_tile}
+
+    def set_launch(self, blocks_per_cu: int = 0, xcd_contiguous: bool = False) -> None:
+        _check("mgwfbp_ctx_set_launch", lib().mgwfbp_ctx_set_launch(self._h, int(blocks_per_cu), int(bool(xcd_contiguous))))
+
+    # ---- device calls: addresses are plain integers ---------------------------------------
+    def pack(self, group: int, d_grad_ptrs: int, d_merge_bufs: int, stream: int = 0) -> None:
+        _check("mgwfbp_pack", lib().mgwfbp_pack(self._h, int(group), _vp(d_grad_ptrs), _vp(d_merge_bufs), _vp(stream)))
+
+    def reduce(self, group: int, d_merge_bufs: int, d_reduced: int, stream: int = 0) -> None:
+        _check("mgwfbp_reduce", lib().mgwfbp_reduce(self._h, int(group), _vp(d_merge_bufs), _vp(d_reduced), _vp(stream)))
+
+    def unpack_update(self, group: int, d_reduced: int, d_w_ptrs: int, d_v_ptrs: int, lr: float, momentum: float,
+                      stream: int = 0) -> None:
+        _check("mgwfbp_unpack_update", lib().mgwfbp_unpack_update(
+            self._h, int(group), _vp(d_reduced), _vp(d_w_ptrs), _vp(d_v_ptrs), float(lr), float(momentum), _vp(stream)))
+
+    def reduce_update(self, group: int, d_merge_bufs: int, d_w_ptrs: int, d_v_ptrs: int, lr: float, momentum: float,
+                      stream: int = 0) -> None:
+        _check("mgwfbp_reduce_update", lib().mgwfbp_reduce_update(
+            self._h, int(group), _vp(d_merge_bufs), _vp(d_w_ptrs), _vp(d_v_ptrs), float(lr), float(momentum), _vp(stream)))
+
+    def group_pipeline(self, group: int, d_grad_ptrs: int, d_merge_bufs: int, d_reduced: int, d_w_ptrs: int,
+                       d_v_ptrs: int, lr: float, momentum: float, stream: int = 0) -> None:
+        _check("mgwfbp_group_pipeline", lib().mgwfbp_group_pipeline(
+            self._h, int(group), _vp(d_grad_ptrs), _vp(d_merge_bufs), _vp(d_reduced or None), _vp(d_w_ptrs),
+            _vp(d_v_ptrs), float(lr), float(momentum), _vp(stream)))

@@ -1,0 +1,692 @@
+// Device side of the MG-WFBP library for gfx950 (MI355X): context management and the streaming
+// kernels pack / reduce / unpack_update and their fused forms.
+//
+// All five operations are the same walk over the merge arena, tile by tile (one workgroup of 256
+// lanes = 4 wavefronts per tile, workgroups stride over tiles):
+//
+//   kind            reads                          writes
+//   PACK            per-layer gradients (P)        merge arenas (P)                     Sec. 5.3
+//   REDUCE          merge arenas (P)               reduced arena                        Eq. 2 (sum, 1/P)
+//   UPDATE          reduced arena, w, v            w, v                                 Eq. 2 (update)
+//   REDUCE_UPDATE   merge arenas (P), w, v         w, v
+//   PIPELINE        per-layer gradients (P), w, v  merge arenas (P), [reduced], w, v
+//
+// The arena side of every access is 16-byte aligned (tiles start on multiples of the tile size and
+// lanes step in 4-element vectors).  The per-layer side starts wherever the tensor starts, so it is
+// accessed through vector types that only promise element alignment; gfx950 executes those as the
+// same 16-byte (8-byte for bfloat16) memory instructions.
+//
+// A tile that lies entirely inside one tensor takes the fast path: tensor index and source offset
+// come from the tile header, the pointer table is read once with wave-uniform addresses, and each
+// lane issues all of its loads (P gradient vectors + w + v, for every vector of the tile) before the
+// first store.  Any other tile takes the general path: the tile-local start offsets of the
+// segments it intersects are produced by a workgroup-wide prefix sum (wavefront scans via
+// cross-lane shifts, combined through LDS) over the segment lengths, staged in LDS, and each lane
+// finds the owner of its vector by binary search there.  Vectors that straddle two tensors or the
+// end of the group fall back to element-wise accesses.
+//
+// This is bandwidth-bound streaming work (at most 4 flops per 12+ bytes), so there is no use for
+// the matrix cores; the job is to keep enough 16-byte requests in flight on every compute unit.
+//
+// Arithmetic contract: binary32, one rounding per operation.  The file must be compiled with
+// -ffp-contract=off so that mu*v + g and w - lr*v are never fused.
+#include <hip/hip_runtime.h>
+
+#include <cstdint>
+#include <cstring>
+#include <new>
+
+#include "mgwfbp.h"
+#include "tables.h"
+
+#ifndef MGWFBP_NT
+#define MGWFBP_NT 3   // bit 0: non-temporal loads of gradients / merge / reduced, bit 1: non-temporal
+                      // stores to merge / reduced, bit 2: non-temporal accesses to w and v
+#endif
+#define MGWFBP_MAXSEG 512   // segments per tile whose offsets are staged in LDS
+
+namespace {
+
+constexpr int BLOCK = MGWFBP_BLOCK;
+constexpr int VEC = MGWFBP_VEC;
+constexpr int TVECS = MGWFBP_TILE_VECS;
+constexpr int TILE = MGWFBP_TILE_ELEMS;
+constexpr int MAXSEG = MGWFBP_MAXSEG;
+
+enum Kind { K_PACK = 0, K_REDUCE = 1, K_UPDATE = 2, K_REDUCE_UPDATE = 3, K_PIPELINE = 4 };
+
+constexpr bool reads_grads(int k) { return k == K_PACK || k == K_PIPELINE; }
+constexpr bool reads_merge(int k) { return k == K_REDUCE || k == K_REDUCE_UPDATE; }
+constexpr bool writes_merge(int k) { return k == K_PACK || k == K_PIPELINE; }
+constexpr bool sums(int k) { return k == K_REDUCE || k == K_REDUCE_UPDATE || k == K_PIPELINE; }
+constexpr bool writes_reduced(int k) { return k == K_REDUCE || k == K_PIPELINE; }
+constexpr bool updates(int k) { return k == K_UPDATE || k == K_REDUCE_UPDATE || k == K_PIPELINE; }
+constexpr bool needs_owner(int k) { return k != K_REDUCE; }
+
+// ---------------------------------------------------------------------------------------------
+// vector types that promise only element alignment
+// ---------------------------------------------------------------------------------------------
+typedef float f32x4 __attribute__((ext_vector_type(4), aligned(4)));
+typedef uint16_t u16x4 __attribute__((ext_vector_type(4), aligned(2)));
+
+template <typename T, int W> struct VecOf;
+template <> struct VecOf<float, 4> { typedef f32x4 type; };
+template <> struct VecOf<float, 1> { typedef float type; };
+template <> struct VecOf<uint16_t, 4> { typedef u16x4 type; };
+template <> struct VecOf<uint16_t, 1> { typedef uint16_t type; };
+
+template <typename V> struct Lanes { static constexpr int n = 4; };
+template <> struct Lanes<float> { static constexpr int n = 1; };
+template <> struct Lanes<uint16_t> { static constexpr int n = 1; };
+
+__device__ __forceinline__ float comp(const f32x4& v, int c) { return v[c]; }
+__device__ __forceinline__ float comp(const float& v, int) { return v; }
+__device__ __forceinline__ uint16_t comp(const u16x4& v, int c) { return v[c]; }
+__device__ __forceinline__ uint16_t comp(const uint16_t& v, int) { return v; }
+__device__ __forceinline__ void setc(f32x4& v, int c, float x) { v[c] = x; }
+__device__ __forceinline__ void setc(float& v, int, float x) { v = x; }
+
+// Address spaces of the AMDGPU target: 1 = global memory, 4 = constant (read-only for the whole
+// kernel; wave-uniform addresses are fetched through the scalar unit).  Pointers that were themselves
+// read from memory carry no address space, so data accesses name it explicitly; otherwise they would
+// become slower generic ("flat") instructions.
+#define MGWFBP_GLOBAL __attribute__((address_space(1)))
+#define MGWFBP_CONST __attribute__((address_space(4)))
+
+template <typename T> __device__ __forceinline__ const MGWFBP_CONST T* ro(const T* p) {
+    return (const MGWFBP_CONST T*)p;
+}
+
+template <bool NT, typename V> __device__ __forceinline__ V ld(const void* p) {
+    const MGWFBP_GLOBAL V* q = (const MGWFBP_GLOBAL V*)p;
+    if constexpr (NT) return __builtin_nontemporal_load(q);
+    else return *q;
+}
+template <bool NT, typename V> __device__ __forceinline__ void st(void* p, const V& x) {
+    MGWFBP_GLOBAL V* q = (MGWFBP_GLOBAL V*)p;
+    if constexpr (NT) __builtin_nontemporal_store(x, q);
+    else *q = x;
+}
+
+constexpr bool NT_LD = (MGWFBP_NT & 1) != 0;
+constexpr bool NT_ST = (MGWFBP_NT & 2) != 0;
+constexpr bool NT_WV = (MGWFBP_NT & 4) != 0;
+
+__device__ __forceinline__ float widen(float x) { return x; }
+__device__ __forceinline__ float widen(uint16_t bits) { return __uint_as_float(static_cast<uint32_t>(bits) << 16); }
+
+// ---------------------------------------------------------------------------------------------
+// kernel arguments
+// ---------------------------------------------------------------------------------------------
+template <typename GradT> struct Args {
+    const TileHdr* tiles;
+    const uint32_t* seg_n;
+    const int32_t* seg_layer;
+    const uint64_t* seg_off;
+    const GradT* const* grad_ptrs;   // [P*L]
+    GradT* const* merge_bufs;        // [P]
+    float* reduced;                  // arena or null
+    float* const* w_ptrs;            // [L]
+    float* const* v_ptrs;            // [L]
+    float lr, mu, inv_p;
+    int32_t L, P;
+    int32_t tile_first, tile_count;
+    int32_t xcd_contiguous;
+};
+
+// Pointers of the P workers, either held in registers (P known at compile time) or re-read from the
+// table on every use (any P).
+template <typename T, int PT> struct WorkerPtrs {
+    T* p[PT];
+    __device__ __forceinline__ void fetch(T* const* table, int64_t stride, int64_t index, int) {
+#pragma unroll
+        for (int w = 0; w < PT; ++w) p[w] = ro(table)[w * stride + index];
+    }
+    __device__ __forceinline__ T* get(int w) const { return p[w]; }
+};
+template <typename T> struct WorkerPtrs<T, 0> {
+    T* const* base;
+    int64_t stride;
+    __device__ __forceinline__ void fetch(T* const* table, int64_t s, int64_t index, int) {
+        base = table + index;
+        stride = s;
+    }
+    __device__ __forceinline__ T* get(int w) const { return ro(base)[w * stride]; }
+};
+
+// Everything one lane holds between its loads and its stores for one vector (W = 4) or element (W = 1).
+template <typename GradT, int PT, int W> struct Regs {
+    typename VecOf<GradT, W>::type g[PT > 0 ? PT : 1];
+    typename VecOf<float, W>::type r, w, v;
+};
+
+// ---------------------------------------------------------------------------------------------
+// load phase / store phase for one vector or element at arena position `apos`, which is element
+// `soff` of its tensor
+// ---------------------------------------------------------------------------------------------
+template <int KIND, typename GradT, int PT, int W>
+__device__ __forceinline__ void load_phase(Regs<GradT, PT, W>& R, const Args<GradT>& A,
+                                           const WorkerPtrs<const GradT, PT>& src,
+                                           const WorkerPtrs<GradT, PT>& mrg,
+                                           const float* wp, const float* vp, int64_t soff, int64_t apos) {
+    typedef typename VecOf<GradT, W>::type GV;
+    typedef typename VecOf<float, W>::type FV;
+    if constexpr (PT > 0) {
+        if constexpr (reads_grads(KIND)) {
+#pragma unroll
+            for (int w = 0; w < PT; ++w) R.g[w] = ld<NT_LD, GV>(src.get(w) + soff);
+        } else if constexpr (reads_merge(KIND)) {
+#pragma unroll
+            for (int w = 0; w < PT; ++w) R.g[w] = ld<NT_LD, GV>(mrg.get(w) + apos);
+        }
+    }
+    if constexpr (KIND == K_UPDATE) R.r = ld<NT_LD, FV>(A.reduced + apos);
+    if constexpr (updates(KIND)) {
+        R.w = ld<NT_WV, FV>(wp + soff);
+        R.v = ld<NT_WV, FV>(vp + soff);
+    }
+}
+
+template <int KIND, typename GradT, int PT, int W>
+__device__ __forceinline__ void store_phase(Regs<GradT, PT, W>& R, const Args<GradT>& A,
+                                            const WorkerPtrs<const GradT, PT>& src,
+                                            const WorkerPtrs<GradT, PT>& mrg,
+                                            float* wp, float* vp, int64_t soff, int64_t apos) {
+    typedef typename VecOf<GradT, W>::type GV;
+    typedef typename VecOf<float, W>::type FV;
+    constexpr int N = Lanes<GV>::n;
+    if constexpr (PT > 0) {
+        if constexpr (writes_merge(KIND)) {
+#pragma unroll
+            for (int w = 0; w < PT; ++w) st<NT_ST, GV>(mrg.get(w) + apos, R.g[w]);
+        }
+        if constexpr (sums(KIND)) {
+#pragma unroll
+            for (int c = 0; c < N; ++c) {
+                float s = widen(comp(R.g[0], c));
+#pragma unroll
+                for (int w = 1; w < PT; ++w) s = s + widen(comp(R.g[w], c));   // worker order 0..P-1
+                setc(R.r, c, s * A.inv_p);
+            }
+        }
+    } else {
+        // any P: stream the workers one after the other (same order, same roundings)
+        FV acc;
+        for (int w = 0; w < A.P; ++w) {
+            GV g;
+            if constexpr (reads_grads(KIND)) g = ld<NT_LD, GV>(src.get(w) + soff);
+            else if constexpr (reads_merge(KIND)) g = ld<NT_LD, GV>(mrg.get(w) + apos);
+            if constexpr (writes_merge(KIND)) st<NT_ST, GV>(mrg.get(w) + apos, g);
+            if constexpr (sums(KIND)) {
+#pragma unroll
+                for (int c = 0; c < N; ++c) {
+                    const float x = widen(comp(g, c));
+                    setc(acc, c, w == 0 ? x : comp(acc, c) + x);
+                }
+            }
+        }
+        if constexpr (sums(KIND)) {
+#pragma unroll
+            for (int c = 0; c < N; ++c) setc(R.r, c, comp(acc, c) * A.inv_p);
+        }
+    }
+    if constexpr (writes_reduced(KIND)) {
+        if (KIND == K_REDUCE || A.reduced != nullptr) st<NT_ST, FV>(A.reduced + apos, R.r);
+    }
+    if constexpr (updates(KIND)) {
+        FV wn, vn;
+#pragma unroll
+        for (int c = 0; c < N; ++c) {
+            const float t1 = A.mu * comp(R.v, c);
+            const float v1 = t1 + comp(R.r, c);
+            const float t2 = A.lr * v1;
+            const float w1 = comp(R.w, c) - t2;
+            setc(vn, c, v1);
+            setc(wn, c, w1);
+        }
+        st<NT_WV, FV>(vp + soff, vn);
+        st<NT_WV, FV>(wp + soff, wn);
+    }
+}
+
+// one vector or element, loads then stores (general path)
+template <int KIND, typename GradT, int PT, int W>
+__device__ __forceinline__ void do_one(const Args<GradT>& A, const WorkerPtrs<GradT, PT>& mrg,
+                                       int layer, int64_t soff, int64_t apos) {
+    WorkerPtrs<const GradT, PT> src;
+    float* wp = nullptr;
+    float* vp = nullptr;
+    if constexpr (reads_grads(KIND)) src.fetch(A.grad_ptrs, A.L, layer, 0);
+    if constexpr (updates(KIND)) {
+        wp = ro(A.w_ptrs)[layer];
+        vp = ro(A.v_ptrs)[layer];
+    }
+    Regs<GradT, PT, W> R;
+    load_phase<KIND, GradT, PT, W>(R, A, src, mrg, wp, vp, soff, apos);
+    store_phase<KIND, GradT, PT, W>(R, A, src, mrg, wp, vp, soff, apos);
+}
+
+// ---------------------------------------------------------------------------------------------
+// fast path: the whole tile belongs to one tensor
+// ---------------------------------------------------------------------------------------------
+template <int KIND, typename GradT, int PT>
+__device__ __forceinline__ void fast_tile(const Args<GradT>& A, const WorkerPtrs<GradT, PT>& mrg,
+                                          int layer, int64_t tensor_off, int64_t tile_base) {
+    WorkerPtrs<const GradT, PT> src;
+    float* wp = nullptr;
+    float* vp = nullptr;
+    if constexpr (reads_grads(KIND)) src.fetch(A.grad_ptrs, A.L, layer, 0);
+    if constexpr (updates(KIND)) {
+        wp = ro(A.w_ptrs)[layer];
+        vp = ro(A.v_ptrs)[layer];
+    }
+    Regs<GradT, PT, VEC> R[TVECS];
+    const int lane_elem = static_cast<int>(threadIdx.x) * VEC;
+#pragma unroll
+    for (int u = 0; u < TVECS; ++u) {
+        const int p = u * (BLOCK * VEC) + lane_elem;
+        load_phase<KIND, GradT, PT, VEC>(R[u], A, src, mrg, wp, vp, tensor_off + p, tile_base + p);
+    }
+#pragma unroll
+    for (int u = 0; u < TVECS; ++u) {
+        const int p = u * (BLOCK * VEC) + lane_elem;
+        store_phase<KIND, GradT, PT, VEC>(R[u], A, src, mrg, wp, vp, tensor_off + p, tile_base + p);
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// general path
+// ---------------------------------------------------------------------------------------------
+
+// Inclusive prefix sum across the 256 lanes of the workgroup: shift-and-add inside each wavefront,
+// wavefront totals combined through LDS.  Every lane of the workgroup must call it.
+__device__ __forceinline__ int block_inclusive_scan(int x, int* s_wave) {
+    const int lane = threadIdx.x & 63;
+    const int wave = threadIdx.x >> 6;
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+        const int y = __shfl_up(x, d, 64);
+        if (lane >= d) x += y;
+    }
+    if (lane == 63) s_wave[wave] = x;
+    __syncthreads();
+    int carry = 0;
+#pragma unroll
+    for (int q = 0; q < BLOCK / 64; ++q)
+        if (q < wave) carry += s_wave[q];
+    return x + carry;
+}
+
+template <int KIND, typename GradT, int PT>
+__device__ void general_tile(const Args<GradT>& A, const WorkerPtrs<GradT, PT>& mrg, const TileHdr& h,
+                             int64_t tile_base, int* s_loc, int* s_layer, int* s_wave) {
+    const int tid = threadIdx.x;
+    const int valid = h.valid;
+    if constexpr (!needs_owner(KIND)) {
+        for (int p = tid * VEC; p < valid; p += BLOCK * VEC) {
+            if (p + VEC <= valid) {
+                do_one<KIND, GradT, PT, VEC>(A, mrg, 0, 0, tile_base + p);
+            } else {
+                for (int q = p; q < valid; ++q) do_one<KIND, GradT, PT, 1>(A, mrg, 0, 0, tile_base + q);
+            }
+        }
+        return;
+    } else {
+        const int nseg = h.nseg;
+        const bool staged = nseg <= MAXSEG;     // uniform over the workgroup
+        if (staged) {
+            __syncthreads();                    // the previous tile's readers are done with LDS
+            // Tile-local start of segment j (1 <= j < nseg) = first_end + sum of the lengths of the
+            // segments 1..j-1, all of which lie wholly inside the tile.  Each lane owns entries
+            // j = 1 + 2*tid and j = 2 + 2*tid.
+            const int j0 = 1 + 2 * tid, j1 = j0 + 1;
+            int x0 = 0, x1 = 0;
+            if (j0 < nseg) x0 = (j0 == 1) ? h.first_end : static_cast<int>(ro(A.seg_n)[h.seg0 + j0 - 1]);
+            if (j1 < nseg) x1 = static_cast<int>(ro(A.seg_n)[h.seg0 + j1 - 1]);
+            const int incl = block_inclusive_scan(x0 + x1, s_wave);
+            if (j0 < nseg) s_loc[j0] = incl - x1;
+            if (j1 < nseg) s_loc[j1] = incl;
+            for (int j = tid; j < nseg; j += BLOCK) s_layer[j] = ro(A.seg_layer)[h.seg0 + j];
+            if (tid == 0) s_loc[nseg] = valid;
+            __syncthreads();
+        }
+        auto start_of = [&](int j) -> int {     // j >= 1
+            return staged ? s_loc[j] : static_cast<int>(static_cast<int64_t>(ro(A.seg_off)[h.seg0 + j]) - tile_base);
+        };
+        auto end_of = [&](int j) -> int { return (j + 1 < nseg) ? start_of(j + 1) : valid; };
+        auto layer_of = [&](int j) -> int { return staged ? s_layer[j] : ro(A.seg_layer)[h.seg0 + j]; };
+        for (int p = tid * VEC; p < valid; p += BLOCK * VEC) {
+            int lo = 0, hi = nseg - 1;          // owner of p: last j with start_of(j) <= p (segment 0 starts <= 0)
+            while (lo < hi) {
+                const int mid = (lo + hi + 1) >> 1;
+                if (start_of(mid) <= p) lo = mid; else hi = mid - 1;
+            }
+            int j = lo;
+            if (p + VEC <= end_of(j)) {
+                const int64_t soff = (j == 0) ? (static_cast<int64_t>(p) - h.first_start)
+                                              : static_cast<int64_t>(p - start_of(j));
+                do_one<KIND, GradT, PT, VEC>(A, mrg, layer_of(j), soff, tile_base + p);
+            } else {
+                for (int q = p; q < p + VEC && q < valid; ++q) {
+                    while (j + 1 < nseg && q >= start_of(j + 1)) ++j;
+                    const int64_t soff = (j == 0) ? (static_cast<int64_t>(q) - h.first_start)
+                                                  : static_cast<int64_t>(q - start_of(j));
+                    do_one<KIND, GradT, PT, 1>(A, mrg, layer_of(j), soff, tile_base + q);
+                }
+            }
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// the kernel
+// ---------------------------------------------------------------------------------------------
+typedef int i32x4 __attribute__((ext_vector_type(4)));
+
+// The 32-byte tile header, fetched as two 16-byte read-only loads (wave-uniform address).
+__device__ __forceinline__ TileHdr load_header(const TileHdr* p) {
+    const MGWFBP_CONST i32x4* q = (const MGWFBP_CONST i32x4*)p;
+    const i32x4 a = q[0], b = q[1];
+    TileHdr h;
+    h.first_start = static_cast<int64_t>((static_cast<uint64_t>(static_cast<uint32_t>(a[1])) << 32) |
+                                         static_cast<uint32_t>(a[0]));
+    h.first_end = a[2];
+    h.seg0 = a[3];
+    h.nseg = b[0];
+    h.valid = b[1];
+    h.layer0 = b[2];
+    h.reserved = b[3];
+    return h;
+}
+
+template <int KIND, typename GradT, int PT>
+__global__ void __launch_bounds__(MGWFBP_BLOCK) mgwfbp_stream_kernel(const Args<GradT> A) {
+    __shared__ int s_loc[MAXSEG + 1];
+    __shared__ int s_layer[MAXSEG];
+    __shared__ int s_wave[BLOCK / 64];
+
+    WorkerPtrs<GradT, PT> mrg;
+    if constexpr (reads_merge(KIND) || writes_merge(KIND)) mrg.fetch(A.merge_bufs, 1, 0, 0);
+
+    int t_begin, t_end, t_step;
+    if (A.xcd_contiguous) {
+        // workgroup ids are dealt round-robin to the 8 dies: die = id % 8.  Give each die one
+        // contiguous eighth of the tiles.
+        const int die = blockIdx.x & 7;
+        const int per_die = (A.tile_count + 7) >> 3;
+        t_begin = die * per_die + static_cast<int>(blockIdx.x >> 3);
+        t_end = min(A.tile_count, (die + 1) * per_die);
+        t_step = static_cast<int>(gridDim.x >> 3);
+    } else {
+        t_begin = blockIdx.x;
+        t_end = A.tile_count;
+        t_step = gridDim.x;
+    }
+    for (int t = t_begin; t < t_end; t += t_step) {
+        const int tile = A.tile_first + t;
+        const TileHdr h = load_header(A.tiles + tile);
+        const int64_t tile_base = static_cast<int64_t>(tile) * TILE;
+        if (h.valid == TILE && (!needs_owner(KIND) || h.nseg == 1)) {
+            fast_tile<KIND, GradT, PT>(A, mrg, h.layer0, -h.first_start, tile_base);
+        } else {
+            general_tile<KIND, GradT, PT>(A, mrg, h, tile_base, s_loc, s_layer, s_wave);
+        }
+    }
+}
+
+thread_local int g_last_hip_error = 0;
+
+int note(hipError_t e) {
+    if (e == hipSuccess) return MGWFBP_OK;
+    g_last_hip_error = static_cast<int>(e);
+    return MGWFBP_EHIP;
+}
+
+}  // namespace
+
+// ---------------------------------------------------------------------------------------------
+// context
+// ---------------------------------------------------------------------------------------------
+struct mgwfbp_ctx {
+    HostTables host;
+    int32_t P = 0;
+    int32_t dtype = 0;
+    bool on_device = false;
+    int device = -1;
+    int n_cu = 0;
+    int32_t blocks_per_cu = 0;
+    int32_t xcd_contiguous = 0;
+    // device copies
+    TileHdr* d_tiles = nullptr;
+    uint32_t* d_seg_n = nullptr;
+    int32_t* d_seg_layer = nullptr;
+    uint64_t* d_seg_off = nullptr;
+};
+
+namespace {
+
+constexpr int32_t DEFAULT_BLOCKS_PER_CU = 8;
+
+template <typename T> int upload(T** dst, const std::vector<T>& src) {
+    const size_t bytes = (src.empty() ? 1 : src.size()) * sizeof(T);
+    hipError_t e = hipMalloc(reinterpret_cast<void**>(dst), bytes);
+    if (e != hipSuccess) {
+        *dst = nullptr;
+        g_last_hip_error = static_cast<int>(e);
+        return e == hipErrorOutOfMemory ? MGWFBP_ENOMEM : MGWFBP_EHIP;
+    }
+    if (!src.empty()) return note(hipMemcpy(*dst, src.data(), src.size() * sizeof(T), hipMemcpyHostToDevice));
+    return MGWFBP_OK;
+}
+
+int create_common(mgwfbp_ctx** out, const uint64_t* n_elems, int32_t L, const uint8_t* merged, int32_t P,
+                  int32_t dtype, bool device) {
+    if (out == nullptr) return MGWFBP_EINVAL;
+    *out = nullptr;
+    if (P < 1 || P > MGWFBP_MAX_P) return MGWFBP_EINVAL;
+    if (dtype != MGWFBP_F32 && dtype != MGWFBP_BF16) return MGWFBP_EINVAL;
+    mgwfbp_ctx* c = new (std::nothrow) mgwfbp_ctx();
+    if (c == nullptr) return MGWFBP_ENOMEM;
+    int rc = mgwfbp_build_tables(n_elems, L, merged, c->host);
+    if (rc != MGWFBP_OK) {
+        delete c;
+        return rc;
+    }
+    c->P = P;
+    c->dtype = dtype;
+    c->blocks_per_cu = DEFAULT_BLOCKS_PER_CU;
+    if (device) {
+        hipDeviceProp_t prop;
+        rc = note(hipGetDevice(&c->device));
+        if (rc == MGWFBP_OK) rc = note(hipGetDeviceProperties(&prop, c->device));
+        if (rc == MGWFBP_OK) {
+            c->n_cu = prop.multiProcessorCount;
+            rc = upload(&c->d_tiles, c->host.tiles);
+        }
+        if (rc == MGWFBP_OK) rc = upload(&c->d_seg_n, c->host.seg_n);
+        if (rc == MGWFBP_OK) rc = upload(&c->d_seg_layer, c->host.seg_layer);
+        if (rc == MGWFBP_OK) rc = upload(&c->d_seg_off, c->host.seg_off);
+        if (rc != MGWFBP_OK) {
+            mgwfbp_ctx_destroy(c);
+            return rc;
+        }
+        c->on_device = true;
+    }
+    *out = c;
+    return MGWFBP_OK;
+}
+
+template <int KIND, typename GradT, int PT>
+int launch_one(const Args<GradT>& A, int grid, hipStream_t stream) {
+    hipLaunchKernelGGL((mgwfbp_stream_kernel<KIND, GradT, PT>), dim3(grid), dim3(BLOCK), 0, stream, A);
+    return note(hipGetLastError());
+}
+
+template <int KIND, typename GradT>
+int launch_by_p(const Args<GradT>& A, int grid, hipStream_t stream) {
+    if constexpr (KIND == K_UPDATE) {
+        return launch_one<KIND, GradT, 0>(A, grid, stream);   // no per-worker data
+    } else {
+        switch (A.P) {
+            case 2: return launch_one<KIND, GradT, 2>(A, grid, stream);
+            case 4: return launch_one<KIND, GradT, 4>(A, grid, stream);
+            case 8: return launch_one<KIND, GradT, 8>(A, grid, stream);
+            case 16: return launch_one<KIND, GradT, 16>(A, grid, stream);
+            default: return launch_one<KIND, GradT, 0>(A, grid, stream);
+        }
+    }
+}
+
+template <int KIND>
+int run(mgwfbp_ctx* c, int32_t group, const void* const* grad_ptrs, void* const* merge_bufs, float* reduced,
+        float* const* w_ptrs, float* const* v_ptrs, float lr, float mu, void* stream_v) {
+    if (c == nullptr || !c->on_device) return MGWFBP_EINVAL;
+    if (group < -1 || group >= c->host.G) return MGWFBP_EINVAL;
+    if (reads_grads(KIND) && grad_ptrs == nullptr) return MGWFBP_EINVAL;
+    if ((reads_merge(KIND) || writes_merge(KIND)) && merge_bufs == nullptr) return MGWFBP_EINVAL;
+    if ((KIND == K_REDUCE || KIND == K_UPDATE) && reduced == nullptr) return MGWFBP_EINVAL;
+    if (updates(KIND) && (w_ptrs == nullptr || v_ptrs == nullptr)) return MGWFBP_EINVAL;
+
+    int32_t t0, t1;
+    if (group < 0) {
+        t0 = 0;
+        t1 = static_cast<int32_t>(c->host.tiles.size());
+    } else {
+        t0 = c->host.group_tile[static_cast<size_t>(group)];
+        t1 = c->host.group_tile[static_cast<size_t>(group) + 1];
+    }
+    const int32_t count = t1 - t0;
+    if (count <= 0) return MGWFBP_OK;             // nothing to move (empty group or empty model)
+
+    int dev = -1;
+    int rc = note(hipGetDevice(&dev));
+    if (rc != MGWFBP_OK) return rc;
+    if (dev != c->device) return MGWFBP_EINVAL;   // tables live on the device the context was made on
+
+    int grid = c->n_cu * c->blocks_per_cu;
+    if (grid > count) grid = count;
+    int32_t xcd = 0;
+    if (c->xcd_contiguous && grid >= 64) {
+        grid &= ~7;
+        xcd = 1;
+    }
+    hipStream_t stream = static_cast<hipStream_t>(stream_v);
+    const float inv_p = 1.0f / static_cast<float>(c->P);
+
+    if (c->dtype == MGWFBP_F32) {
+        Args<float> A{c->d_tiles, c->d_seg_n, c->d_seg_layer, c->d_seg_off,
+                      reinterpret_cast<const float* const*>(grad_ptrs),
+                      reinterpret_cast<float* const*>(merge_bufs), reduced, w_ptrs, v_ptrs,
+                      lr, mu, inv_p, c->host.L, c->P, t0, count, xcd};
+        return launch_by_p<KIND, float>(A, grid, stream);
+    }
+    Args<uint16_t> A{c->d_tiles, c->d_seg_n, c->d_seg_layer, c->d_seg_off,
+                     reinterpret_cast<const uint16_t* const*>(grad_ptrs),
+                     reinterpret_cast<uint16_t* const*>(merge_bufs), reduced, w_ptrs, v_ptrs,
+                     lr, mu, inv_p, c->host.L, c->P, t0, count, xcd};
+    return launch_by_p<KIND, uint16_t>(A, grid, stream);
+}
+
+}  // namespace
+
+extern "C" {
+
+int mgwfbp_ctx_create(mgwfbp_ctx** ctx_out, const uint64_t* n_elems, int32_t L, const uint8_t* merged,
+                      int32_t P, int32_t grad_dtype) {
+    return create_common(ctx_out, n_elems, L, merged, P, grad_dtype, true);
+}
+
+int mgwfbp_ctx_create_host(mgwfbp_ctx** ctx_out, const uint64_t* n_elems, int32_t L, const uint8_t* merged,
+                           int32_t P, int32_t grad_dtype) {
+    return create_common(ctx_out, n_elems, L, merged, P, grad_dtype, false);
+}
+
+void mgwfbp_ctx_destroy(mgwfbp_ctx* c) {
+    if (c == nullptr) return;
+    if (c->d_tiles) (void)hipFree(c->d_tiles);
+    if (c->d_seg_n) (void)hipFree(c->d_seg_n);
+    if (c->d_seg_layer) (void)hipFree(c->d_seg_layer);
+    if (c->d_seg_off) (void)hipFree(c->d_seg_off);
+    delete c;
+}
+
+int mgwfbp_ctx_dims(const mgwfbp_ctx* c, int32_t* L, int32_t* n_groups, int32_t* P, int32_t* grad_dtype,
+                    uint64_t* arena_elems, int32_t* tile_elems, int32_t* n_tiles) {
+    if (c == nullptr) return MGWFBP_EINVAL;
+    if (L) *L = c->host.L;
+    if (n_groups) *n_groups = c->host.G;
+    if (P) *P = c->P;
+    if (grad_dtype) *grad_dtype = c->dtype;
+    if (arena_elems) *arena_elems = c->host.arena_elems;
+    if (tile_elems) *tile_elems = TILE;
+    if (n_tiles) *n_tiles = static_cast<int32_t>(c->host.tiles.size());
+    return MGWFBP_OK;
+}
+
+int mgwfbp_ctx_layout(const mgwfbp_ctx* c, uint64_t* tensor_off, int32_t* tensor_group, uint64_t* group_base,
+                      uint64_t* group_elems) {
+    if (c == nullptr) return MGWFBP_EINVAL;
+    const HostTables& h = c->host;
+    if (tensor_off && h.L) std::memcpy(tensor_off, h.tensor_off.data(), sizeof(uint64_t) * static_cast<size_t>(h.L));
+    if (tensor_group && h.L) std::memcpy(tensor_group, h.tensor_group.data(), sizeof(int32_t) * static_cast<size_t>(h.L));
+    if (group_base && h.G) std::memcpy(group_base, h.group_base.data(), sizeof(uint64_t) * static_cast<size_t>(h.G));
+    if (group_elems && h.G) std::memcpy(group_elems, h.group_elems.data(), sizeof(uint64_t) * static_cast<size_t>(h.G));
+    return MGWFBP_OK;
+}
+
+int mgwfbp_ctx_tables(const mgwfbp_ctx* c, int32_t* n_segments, void* tiles_out, uint64_t* seg_off_out,
+                      uint32_t* seg_n_out, int32_t* seg_layer_out, int32_t* group_tile_out) {
+    if (c == nullptr) return MGWFBP_EINVAL;
+    const HostTables& h = c->host;
+    const size_t S = h.seg_layer.size();
+    if (n_segments) *n_segments = static_cast<int32_t>(S);
+    if (tiles_out && !h.tiles.empty()) std::memcpy(tiles_out, h.tiles.data(), sizeof(TileHdr) * h.tiles.size());
+    if (seg_off_out) std::memcpy(seg_off_out, h.seg_off.data(), sizeof(uint64_t) * (S + 1));
+    if (seg_n_out && S) std::memcpy(seg_n_out, h.seg_n.data(), sizeof(uint32_t) * S);
+    if (seg_layer_out && S) std::memcpy(seg_layer_out, h.seg_layer.data(), sizeof(int32_t) * S);
+    if (group_tile_out) std::memcpy(group_tile_out, h.group_tile.data(), sizeof(int32_t) * h.group_tile.size());
+    return MGWFBP_OK;
+}
+
+int mgwfbp_ctx_set_launch(mgwfbp_ctx* c, int32_t blocks_per_cu, int32_t xcd_contiguous) {
+    if (c == nullptr || blocks_per_cu > 4096) return MGWFBP_EINVAL;
+    c->blocks_per_cu = blocks_per_cu <= 0 ? DEFAULT_BLOCKS_PER_CU : blocks_per_cu;
+    c->xcd_contiguous = xcd_contiguous ? 1 : 0;
+    return MGWFBP_OK;
+}
+
+int mgwfbp_pack(mgwfbp_ctx* c, int32_t group, const void* const* d_grad_ptrs, void* const* d_merge_bufs,
+                void* hip_stream) {
+    return run<K_PACK>(c, group, d_grad_ptrs, d_merge_bufs, nullptr, nullptr, nullptr, 0.f, 0.f, hip_stream);
+}
+
+int mgwfbp_reduce(mgwfbp_ctx* c, int32_t group, const void* const* d_merge_bufs, float* d_reduced,
+                  void* hip_stream) {
+    return run<K_REDUCE>(c, group, nullptr, const_cast<void* const*>(d_merge_bufs), d_reduced, nullptr, nullptr,
+                         0.f, 0.f, hip_stream);
+}
+
+int mgwfbp_unpack_update(mgwfbp_ctx* c, int32_t group, const float* d_reduced, float* const* d_w_ptrs,
+                         float* const* d_v_ptrs, float lr, float momentum, void* hip_stream) {
+    return run<K_UPDATE>(c, group, nullptr, nullptr, const_cast<float*>(d_reduced), d_w_ptrs, d_v_ptrs, lr,
+                         momentum, hip_stream);
+}
+
+int mgwfbp_reduce_update(mgwfbp_ctx* c, int32_t group, const void* const* d_merge_bufs, float* const* d_w_ptrs,
+                         float* const* d_v_ptrs, float lr, float momentum, void* hip_stream) {
+    return run<K_REDUCE_UPDATE>(c, group, nullptr, const_cast<void* const*>(d_merge_bufs), nullptr, d_w_ptrs,
+                                d_v_ptrs, lr, momentum, hip_stream);
+}
+
+int mgwfbp_group_pipeline(mgwfbp_ctx* c, int32_t group, const void* const* d_grad_ptrs, void* const* d_merge_bufs,
+                          float* d_reduced, float* const* d_w_ptrs, float* const* d_v_ptrs, float lr,
+                          float momentum, void* hip_stream) {
+    return run<K_PIPELINE>(c, group, d_grad_ptrs, d_merge_bufs, d_reduced, d_w_ptrs, d_v_ptrs, lr, momentum,
+                           hip_stream);
+}
+
+int mgwfbp_last_hip_error(void) { return g_last_hip_error; }
+
+const char* mgwfbp_version(void) { return "mgwfbp-gfx950 0.1"; }
+
+}  // extern "C"

@@ -1,0 +1,86 @@
+"""mgwfbp_plan / mgwfbp_eval (host code of the library) against the oracle: bit-exact."""
+import numpy as np
+import pytest
+
+import paper_1912_09268_amd as M
+import workloads as W
+from oracle import plan as OP
+
+
+def _lists(p):
+    return [int(x) for x in p.size_bytes], [float(x) for x in p.t_backward]
+
+
+@pytest.mark.parametrize("name", W.PROFILE_NAMES)
+def test_plan_matches_oracle_on_profiles(name):
+    p = W.make_profile(name)
+    by, tb = _lists(p)
+    merged, first = M.plan(p.size_bytes, p.t_backward, p.a, p.b)
+    ref = OP.plan_algorithm1(by, tb, p.a, p.b)
+    assert merged.tolist() == ref
+    groups = OP.groups_in_arrival_order(ref)
+    assert first.tolist() == [g[0] for g in groups]
+    t = M.eval_plan(merged, p.size_bytes, p.t_backward, p.a, p.b)
+    assert t == OP.iteration_time(ref, by, tb, p.a, p.b)          # same bits
+
+
+def test_plan_matches_oracle_on_random_instances():
+    rng = np.random.default_rng(11)
+    n_merge = 0
+    for trial in range(1500):
+        L = int(rng.integers(1, 40))
+        wide = trial % 3 == 0
+        p = W.make_random_profile(rng, L, size_hi=10 ** 6 if wide else 5000, tb_hi=5e-3 if wide else 500e-6,
+                                  allow_empty=True)
+        by, tb = _lists(p)
+        merged, first = M.plan(p.size_bytes, p.t_backward, p.a, p.b)
+        ref = OP.plan_algorithm1(by, tb, p.a, p.b)
+        assert merged.tolist() == ref, (trial, L)
+        n_merge += sum(ref)
+        assert M.eval_plan(merged, p.size_bytes, p.t_backward, p.a, p.b) == OP.iteration_time(ref, by, tb, p.a, p.b)
+    assert n_merge > 1000          # the comparison saw plenty of merges, not only all-normal plans
+
+
+def test_eval_matches_oracle_on_arbitrary_plans():
+    rng = np.random.default_rng(12)
+    for _ in range(500):
+        L = int(rng.integers(1, 30))
+        p = W.make_random_profile(rng, L)
+        by, tb = _lists(p)
+        m = [0] + [int(x) for x in rng.integers(0, 2, size=L - 1)]
+        assert M.eval_plan(m, p.size_bytes, p.t_backward, p.a, p.b) == OP.iteration_time(m, by, tb, p.a, p.b)
+
+
+def test_plan_hand_example_and_equality_case():
+    merged, first = M.plan([0, 0, 100], [49.1, 0.9, 0.0], 1.0, 1.0)
+    assert merged.tolist() == [0, 0, 1] and first.tolist() == [2, 0]
+    assert M.eval_plan(merged, [0, 0, 100], [49.1, 0.9, 0.0], 1.0, 1.0) == pytest.approx(102.9)
+    merged, _ = M.plan([7, 5], [10.0, 3.0], 10.0, 1.0)          # wait == a -> stays normal
+    assert merged.tolist() == [0, 0]
+
+
+def test_plan_degenerate_and_invalid_inputs():
+    merged, first = M.plan([], [], 1.0, 1.0)
+    assert merged.size == 0 and first.size == 0
+    merged, first = M.plan([12], [0.5], 1.0, 1.0)
+    assert merged.tolist() == [0] and first.tolist() == [0]
+    merged, _ = M.plan([4, 4, 4], [1.0, 1.0, 1.0], 0.0, 0.0)
+    assert merged.tolist() == [0, 0, 0]
+    for bad in ((float("nan"), 1.0), (-1.0, 1.0), (1.0, float("inf")), (1.0, -2.0)):
+        with pytest.raises(M.MgwfbpError):
+            M.plan([4, 4], [1.0, 1.0], *bad)
+    with pytest.raises(M.MgwfbpError):
+        M.plan([4, 4], [1.0, -1.0], 1.0, 1.0)
+    with pytest.raises(M.MgwfbpError):
+        M.plan([2 ** 63, 2 ** 63], [1.0, 1.0], 1.0, 1.0)       # merged size would wrap
+    with pytest.raises(M.MgwfbpError):
+        M.eval_plan([1, 0], [4, 4], [1.0, 1.0], 1.0, 1.0)      # layer 1 cannot be merged
+
+
+def test_plan_time_scales_linearly():
+    import time
+    rng = np.random.default_rng(13)
+    p = W.make_random_profile(rng, 20000)
+    t0 = time.perf_counter()
+    M.plan(p.size_bytes, p.t_backward, p.a, p.b)
+    assert time.perf_counter() - t0 < 0.5
