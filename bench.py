@@ -1,0 +1,200 @@
+"""Benchmark of the merged-gradient hot path on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload resnet50] [--mode pipeline]
+
+A step is one pass of the whole device path over one synthetic batch of gradients: every group of the
+plan is packed into the P merge arenas, reduced (sum over the P simulated workers, times 1/P) and
+applied to the per-layer weights and momenta.  Inputs are resident in HBM before the timed region.
+The plan itself is computed once per training run; its time is reported separately as `plan_us`.
+
+Prints ONE JSON line.  `value` is algorithmic bytes of the path that ran divided by the time per step.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import statistics
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0
+
+
+def bytes_per_element(mode: str, P: int, g: int) -> int:
+    """Algorithmic HBM bytes per gradient element for the path a mode runs (g = gradient bytes).
+    pack 2*P*g | reduce P*g + 4 | unpack_update 20 | fused forms drop the intermediate traffic."""
+    if mode in ("pipeline", "pipeline_per_group"):
+        return 2 * P * g + 16            # read P grads, write P merge, read+write w and v
+    if mode == "reduce_update":
+        return 2 * P * g + (P * g + 16)  # pack, then merge -> w, v
+    if mode in ("staged", "staged_per_group"):
+        return 3 * P * g + 24
+    raise KeyError(mode)
+
+
+def launches_per_step(mode: str, G: int) -> int:
+    return {"pipeline": 1, "pipeline_per_group": G, "reduce_update": 2, "staged": 3, "staged_per_group": 3 * G}[mode]
+
+
+def run_step(dm, mode: str, lr: float, mu: float, G: int) -> None:
+    if mode == "pipeline":
+        dm.group_pipeline(lr, mu, -1, write_reduced=False)
+    elif mode == "pipeline_per_group":
+        for k in range(G):
+            dm.group_pipeline(lr, mu, k, write_reduced=False)
+    elif mode == "reduce_update":
+        dm.pack(-1); dm.reduce_update(lr, mu, -1)
+    elif mode == "staged":
+        dm.pack(-1); dm.reduce(-1); dm.unpack_update(lr, mu, -1)
+    elif mode == "staged_per_group":
+        for k in range(G):
+            dm.pack(k); dm.reduce(k); dm.unpack_update(lr, mu, k)
+    else:
+        raise KeyError(mode)
+
+
+def time_mode(dm, mode, lr, mu, G, steps, warmup):
+    """Returns (wall ms per step, HIP-event ms per step).  Events sit on torch's current stream, which
+    is the stream handed to the library."""
+    import torch
+    for _ in range(warmup):
+        run_step(dm, mode, lr, mu, G)
+    torch.cuda.synchronize()
+    e0 = torch.cuda.Event(enable_timing=True)
+    e1 = torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    e0.record()
+    for _ in range(steps):
+        run_step(dm, mode, lr, mu, G)
+    e1.record()
+    torch.cuda.synchronize()
+    wall = (time.perf_counter() - t0) * 1e3 / steps
+    return wall, e0.elapsed_time(e1) / steps
+
+
+def cpu_baseline(profile, merged, bytes_per_step, budget_s=10.0):
+    """The oracle as it stands, timed on this host for whole steps until `budget_s` is used up."""
+    import numpy as np
+    import workloads as W
+    from oracle import pipeline as OD
+    from oracle import plan as OP
+    groups = OP.groups_in_arrival_order([int(x) for x in merged])
+    flats = [W.worker_gradient_flat(profile, w) for w in range(profile.P)]
+    grads = [W.split_by_layer(f, profile.n_elems) for f in flats]
+    w = [x.copy() for x in W.split_by_layer(W.initial_weights_flat(profile), profile.n_elems)]
+    v = [x.copy() for x in W.split_by_layer(W.initial_momentum_flat(profile), profile.n_elems)]
+    times = []
+    t_all = time.perf_counter()
+    while not times or (time.perf_counter() - t_all < budget_s and len(times) < 20):
+        t0 = time.perf_counter()
+        OD.merged_step(grads, groups, w, v, profile.lr, profile.momentum)
+        times.append(time.perf_counter() - t0)
+    best = min(times)
+    return {"value": bytes_per_step / best / 1e9, "unit": "GB/s", "cores": 1, "kind": "oracle",
+            "sample": f"{len(times)} full step(s) of the {profile.name} workload (all groups, P={profile.P}); "
+                      f"best {best * 1e3:.0f} ms/step; same byte count as `value`",
+            "ms_per_step": best * 1e3, "host_cpus": os.cpu_count()}
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default="resnet50")
+    ap.add_argument("--mode", default="pipeline",
+                    choices=["pipeline", "pipeline_per_group", "reduce_update", "staged", "staged_per_group"])
+    ap.add_argument("--all-modes", action="store_true", help="also time the other launch modes (extra keys)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--blocks-per-cu", type=int, default=0)
+    ap.add_argument("--xcd-contiguous", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (the path is per-GPU; nothing is sharded or "
+              "exchanged between GPUs). Run with --gpus 1.", file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+
+    import paper_1912_09268_amd as M
+    import workloads as W
+    from paper_1912_09268_amd import harness as H
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 2
+    torch.cuda.set_device(0)
+
+    p = W.make_profile(args.workload)
+    n = [int(x) for x in p.n_elems]
+    g = p.elem_bytes
+
+    # plan: one-time host computation, timed on its own
+    plan_times = []
+    for _ in range(1000 if p.L <= 1000 else 100):
+        t0 = time.perf_counter()
+        merged, first = M.plan(p.size_bytes, p.t_backward, p.a, p.b)
+        plan_times.append((time.perf_counter() - t0) * 1e6)
+    plan_us = statistics.median(plan_times)
+    G = int(first.shape[0])
+
+    ctx = M.Context(n, merged, p.P, M.BF16 if p.grad_dtype == "bf16" else M.F32)
+    ctx.set_launch(args.blocks_per_cu, args.xcd_contiguous)
+    dm = H.DeviceModel(ctx, n)
+    for w in range(p.P):
+        dm.upload_grads(w, W.worker_gradient_flat(p, w))
+    dm.upload_weights(W.initial_weights_flat(p), W.initial_momentum_flat(p, zero=True))
+    torch.cuda.synchronize()
+
+    E = p.total_elems
+    wall_ms, event_ms = time_mode(dm, args.mode, p.lr, p.momentum, G, args.steps, args.warmup)
+    bpe = bytes_per_element(args.mode, p.P, g)
+    step_bytes = bpe * E
+    value = step_bytes / (wall_ms * 1e-3) / 1e9
+    nl = launches_per_step(args.mode, G)
+    kernel_ms = event_ms / nl
+    achieved = (step_bytes / nl) / (kernel_ms * 1e-3) / 1e9
+
+    out = {
+        "metric": "pack+reduce+unpack GB/s and % of HBM peak on 1 MI355X; plan time (us)",
+        "value": round(value, 1), "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(wall_ms, 5), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32" if g == 4 else "bf16 gradients, f32 accumulate/update", "data": "synthetic",
+        "config": {"workload": args.workload, "tensors": p.L, "elements": E, "groups": G, "P": p.P,
+                   "mode": args.mode, "launches_per_step": nl, "bytes_per_element": bpe,
+                   "tile_elems": ctx.tile_elems, "blocks_per_cu": args.blocks_per_cu or "default",
+                   "xcd_contiguous": bool(args.xcd_contiguous)},
+        "pct_of_hbm_peak": round(100.0 * value / HBM_PEAK_GBPS, 2),
+        "plan_us": round(plan_us, 2),
+        "roofline": {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                     "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": None,
+                     "kernel": f"mgwfbp_stream_kernel<{args.mode}>", "avg_launch_ms": round(kernel_ms, 5),
+                     "algorithmic_bytes_per_launch": step_bytes // nl},
+    }
+    if args.all_modes:
+        others = {}
+        for mode in ("pipeline", "pipeline_per_group", "reduce_update", "staged", "staged_per_group"):
+            if mode == args.mode:
+                continue
+            k = max(10, args.steps // (4 if mode.endswith("per_group") else 1))
+            wl, ev = time_mode(dm, mode, p.lr, p.momentum, G, k, max(2, args.warmup // 4))
+            b = bytes_per_element(mode, p.P, g) * E
+            others[mode] = {"ms_per_step": round(wl, 5), "GBps": round(b / (wl * 1e-3) / 1e9, 1),
+                            "bytes_per_element": bytes_per_element(mode, p.P, g),
+                            "launches_per_step": launches_per_step(mode, G)}
+        out["other_modes"] = others
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(p, merged, step_bytes)
+    ctx.close()
+    print(json.dumps(out))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -1,0 +1,251 @@
+"""HIP path against the CPU oracle, element by element, through the C ABI.  Everything here is
+bit-exact: pack is a copy, and reduce / update fix the operation order and rounding."""
+import sys
+import time
+
+import numpy as np
+import pytest
+
+import workloads as W
+from oracle import pipeline as OD
+from oracle import plan as OP
+
+pytestmark = pytest.mark.gpu
+
+MODES = ("staged", "staged_per_group", "reduce_update", "pipeline", "pipeline_per_group", "pipeline_no_reduced")
+
+
+def _say(msg):
+    print(msg, flush=True)
+    sys.stdout.flush()
+
+
+def _bits(a):
+    a = np.ascontiguousarray(a)
+    return a.view(np.uint32) if a.dtype == np.float32 else a.view(np.uint16)
+
+
+def _run_mode(dm, mode, lr, mu, G):
+    if mode == "staged":
+        dm.pack(); dm.reduce(); dm.unpack_update(lr, mu)
+    elif mode == "staged_per_group":
+        for k in range(G):
+            dm.pack(k); dm.reduce(k); dm.unpack_update(lr, mu, k)
+    elif mode == "reduce_update":
+        dm.pack(); dm.reduce_update(lr, mu)
+    elif mode == "pipeline":
+        dm.group_pipeline(lr, mu)
+    elif mode == "pipeline_per_group":
+        for k in reversed(range(G)):          # groups are independent: any order gives the same bits
+            dm.group_pipeline(lr, mu, k)
+    elif mode == "pipeline_no_reduced":
+        dm.group_pipeline(lr, mu, write_reduced=False)
+    else:
+        raise KeyError(mode)
+
+
+def check_case(profile, merged, mode, misalign=0, steps=1, seed=W.BASE_SEED, label=""):
+    """Run `steps` iterations on the GPU and in the oracle from the same host arrays and compare every
+    output: P merge arenas, the reduced arena, weights and momenta, and the padding of the arenas."""
+    import torch
+    import paper_1912_09268_amd as M
+    from paper_1912_09268_amd import harness as H
+
+    _say(f"[parity] {label or profile.name} L={profile.L} E={profile.total_elems} P={profile.P} "
+         f"{profile.grad_dtype} mode={mode} misalign={misalign} seed={seed}")
+    n = [int(x) for x in profile.n_elems]
+    merged = [int(x) for x in merged]
+    gdt = M.BF16 if profile.grad_dtype == "bf16" else M.F32
+    ctx = M.Context(n, merged, profile.P, gdt)
+    dm = H.DeviceModel(ctx, n, misalign=misalign, fill_arena=True)
+    off, grp, base, ge = ctx.layout()
+    groups = OP.groups_in_arrival_order(merged)
+    assert len(groups) == ctx.n_groups
+
+    w_flat = W.initial_weights_flat(profile, seed)
+    v_flat = W.initial_momentum_flat(profile, seed)
+    dm.upload_weights(w_flat, v_flat)
+    w_o = [x.copy() for x in W.split_by_layer(w_flat, profile.n_elems)]
+    v_o = [x.copy() for x in W.split_by_layer(v_flat, profile.n_elems)]
+
+    for step in range(steps):
+        flats = [W.worker_gradient_flat(profile, w, seed + 1000 * step) for w in range(profile.P)]
+        for w in range(profile.P):
+            dm.upload_grads(w, flats[w])
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        _run_mode(dm, mode, profile.lr, profile.momentum, ctx.n_groups)
+        torch.cuda.synchronize()
+        _say(f"[parity]   step {step}: device calls took {1e3 * (time.perf_counter() - t0):.2f} ms")
+
+        grads = [W.split_by_layer(f, profile.n_elems) for f in flats]
+        merge_dev = [dm.download_merge(w) for w in range(profile.P)]
+        red_dev = dm.download_reduced()
+        covered = np.zeros(max(ctx.arena_elems, 1), bool)
+        red_o = []
+        for k, members in enumerate(groups):
+            lo, hi = int(base[k]), int(base[k]) + int(ge[k])
+            covered[lo:hi] = True
+            bufs = [OD.pack(grads[w], [members])[0] for w in range(profile.P)]
+            for w in range(profile.P):
+                assert np.array_equal(_bits(merge_dev[w][lo:hi]), _bits(bufs[w])), f"merge arena w={w} group={k}"
+            r = OD.reduce_average(bufs)
+            red_o.append(r)
+            if mode not in ("reduce_update", "pipeline_no_reduced"):
+                assert np.array_equal(_bits(red_dev[lo:hi]), _bits(r)), f"reduced group={k}"
+        # padding between groups is never written
+        pad = ~covered
+        for w in range(profile.P):
+            m = _bits(merge_dev[w])
+            sent = H.SENTINEL32 if m.dtype == np.uint32 else H.SENTINEL16
+            assert (m[pad] == sent).all(), "merge arena padding was written"
+        r32 = _bits(red_dev)
+        assert (r32[pad] == H.SENTINEL32).all(), "reduced arena padding was written"
+        if mode in ("reduce_update", "pipeline_no_reduced"):
+            assert (r32 == H.SENTINEL32).all(), "reduced arena must stay untouched in this mode"
+        OD.unpack_update(red_o, groups, w_o, v_o, profile.lr, profile.momentum)
+        w_dev = dm.download_weights()
+        v_dev = dm.download_momenta()
+        w_ref = np.concatenate(w_o) if w_o else np.zeros(0, np.float32)
+        v_ref = np.concatenate(v_o) if v_o else np.zeros(0, np.float32)
+        assert np.array_equal(_bits(v_dev), _bits(v_ref)), "momentum"
+        assert np.array_equal(_bits(w_dev), _bits(w_ref)), "weights"
+        dm.fill_arenas()
+    ctx.close()
+
+
+def _plan_of(profile):
+    import paper_1912_09268_amd as M
+    merged, _ = M.plan(profile.size_bytes, profile.t_backward, profile.a, profile.b)
+    ref = OP.plan_algorithm1([int(x) for x in profile.size_bytes], [float(x) for x in profile.t_backward],
+                             profile.a, profile.b)
+    assert merged.tolist() == ref
+    return ref
+
+
+# ------------------------------------------------------------------------------------------
+# small and medium cases: several tiles, ragged tails, every mode
+# ------------------------------------------------------------------------------------------
+
+@pytest.mark.parametrize("mode", MODES)
+def test_toy_mlp_all_modes(mode):
+    p = W.make_profile("toy_mlp")
+    check_case(p, _plan_of(p), mode, steps=2)
+
+
+@pytest.mark.parametrize("P", [1, 2, 3, 4, 8, 16])
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_random_models_worker_counts(P, dtype):
+    rng = np.random.default_rng(1000 + P)
+    p = W.make_random_profile(rng, 50, size_hi=20000, P=P, grad_dtype=dtype, allow_empty=True)
+    merged = [0] + [int(x) for x in (rng.random(p.L - 1) < 0.6)]
+    for mode in ("staged", "pipeline", "reduce_update"):
+        check_case(p, merged, mode, label=f"random P={P}")
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("mode", ["staged", "pipeline"])
+def test_misaligned_sources_and_odd_sizes(dtype, mode):
+    rng = np.random.default_rng(7)
+    p = W.make_random_profile(rng, 80, size_lo=1, size_hi=9000, P=4, grad_dtype=dtype)
+    merged = [0] + [int(x) for x in (rng.random(p.L - 1) < 0.7)]
+    check_case(p, merged, mode, misalign=3, steps=2, label="misaligned")
+
+
+@pytest.mark.parametrize("mode", ["staged", "pipeline"])
+def test_thousands_of_one_element_tensors(mode):
+    """More segments in one tile than the kernel stages in LDS, plus straddling vectors everywhere."""
+    sizes = [1] * 3000 + [5, 1, 1, 7] * 50 + [4100, 3]
+    rng = np.random.default_rng(8)
+    p = W.Profile("ones", np.asarray(sizes, np.uint64), rng.uniform(1e-6, 1e-5, len(sizes)), 1e-4, 1e-9, 2,
+                  "f32", 1.0)
+    merged = [0] + [1] * (len(sizes) - 1)
+    check_case(p, merged, mode)
+    merged = [0] + [int(x) for x in (rng.random(len(sizes) - 1) < 0.97)]
+    check_case(p, merged, mode)
+
+
+def test_single_layer_and_all_normal_and_all_merged():
+    rng = np.random.default_rng(9)
+    one = W.Profile("one", np.asarray([70001], np.uint64), np.asarray([1e-3]), 1e-5, 1e-9, 8, "f32", 1.0)
+    check_case(one, [0], "pipeline")
+    check_case(one, [0], "staged")
+    p = W.make_random_profile(rng, 12, size_hi=30000, P=8)
+    check_case(p, [0] * p.L, "pipeline", label="all normal")
+    check_case(p, [0] + [1] * (p.L - 1), "pipeline", label="all merged")
+    check_case(p, [0] + [1] * (p.L - 1), "staged_per_group", label="all merged")
+
+
+def test_empty_model_and_empty_groups_are_no_ops():
+    empty = W.Profile("empty", np.zeros(3, np.uint64), np.asarray([1e-3] * 3), 1e-5, 1e-9, 2, "f32", 1.0)
+    check_case(empty, [0, 1, 0], "staged")
+    check_case(empty, [0, 1, 0], "pipeline_per_group")
+    mixed = W.Profile("mixed", np.asarray([0, 0, 9, 0, 5000, 0], np.uint64), np.asarray([1e-3] * 6), 1e-5, 1e-9, 2,
+                      "f32", 1.0)
+    check_case(mixed, [0, 1, 0, 0, 1, 0], "staged_per_group")
+    check_case(mixed, [0, 1, 0, 0, 1, 0], "pipeline")
+
+
+def test_special_values_propagate_like_ieee():
+    """Subnormals, signed zeros, infinities and NaNs go through pack untouched and through reduce /
+    update with IEEE semantics (no flush to zero)."""
+    import torch
+    import paper_1912_09268_amd as M
+    from paper_1912_09268_amd import harness as H
+    n = [5000]
+    ctx = M.Context(n, [0], 2, M.F32)
+    dm = H.DeviceModel(ctx, n, fill_arena=True)
+    g0 = np.full(5000, 1e-40, np.float32)           # subnormal
+    g1 = np.full(5000, 2e-40, np.float32)
+    g0[1], g1[1] = np.inf, 1.0
+    g0[2], g1[2] = np.inf, -np.inf                  # NaN
+    g0[3], g1[3] = -0.0, -0.0
+    g0[4], g1[4] = 3.0e38, 3.0e38                   # overflows to +inf in the sum
+    w = np.ones(5000, np.float32)
+    v = np.full(5000, 1e-41, np.float32)
+    dm.upload_grads(0, g0); dm.upload_grads(1, g1); dm.upload_weights(w, v)
+    dm.group_pipeline(0.1, 0.9)
+    torch.cuda.synchronize()
+    bufs = [g0, g1]
+    r = OD.reduce_average(bufs)
+    wo, vo = w.copy(), v.copy()
+    OD.sgd_momentum(wo, vo, r, 0.1, 0.9)
+    def same(dev, ref):
+        # IEEE 754 fixes which results are NaN but not a NaN's sign or payload: compare NaN positions,
+        # and bits everywhere else
+        nan = np.isnan(ref)
+        return np.array_equal(np.isnan(dev), nan) and np.array_equal(_bits(dev)[~nan], _bits(ref)[~nan])
+
+    assert np.array_equal(_bits(dm.download_merge(0)[:5000]), _bits(g0))       # a copy keeps every bit
+    assert same(dm.download_reduced()[:5000], r)
+    assert same(dm.download_momenta(), vo)
+    assert same(dm.download_weights(), wo)
+    assert r[0] != 0 and np.isnan(r[2]) and np.isinf(r[4])
+    ctx.close()
+
+
+def test_device_entry_points_reject_bad_arguments():
+    import paper_1912_09268_amd as M
+    from paper_1912_09268_amd import harness as H
+    ctx = M.Context([100, 100], [0, 1], 2, M.F32)
+    dm = H.DeviceModel(ctx, [100, 100])
+    with pytest.raises(M.MgwfbpError):
+        dm.pack(5)                                   # group out of range
+    with pytest.raises(M.MgwfbpError):
+        ctx.pack(0, 0, dm.merge_ptrs.data_ptr())     # null pointer table
+    with pytest.raises(M.MgwfbpError):
+        ctx.reduce(0, dm.merge_ptrs.data_ptr(), 0)   # null reduced arena
+    ctx.close()
+
+
+# ------------------------------------------------------------------------------------------
+# the benchmark configurations at full size, in the launch configuration bench.py times
+# ------------------------------------------------------------------------------------------
+
+@pytest.mark.parametrize("name,mode", [("resnet50", "pipeline"), ("resnet50", "staged"),
+                                       ("tiny_layers", "pipeline"), ("tiny_layers", "staged_per_group"),
+                                       ("vgg16", "pipeline"), ("vgg16", "staged"),
+                                       ("transformer", "pipeline"), ("transformer", "staged")])
+def test_full_size_profiles(name, mode):
+    p = W.make_profile(name)
+    check_case(p, _plan_of(p), mode, steps=1)
