@@ -24,6 +24,14 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBPS = 8000.0
 
+# HBM-side bytes per launch measured with rocprofv3 (--pmc FETCH_SIZE, then --pmc WRITE_SIZE, each scaled
+# by the same counter's reading for a plain 1 GiB device copy); the runs and the scale factors are in
+# profiles/mgwfbp_stream_kernel_<workload>_<mode>.txt.  Only the single-kernel mode has one figure.
+MEASURED_TRAFFIC_BYTES = {
+    ("resnet50", "pipeline"): 2.0466e9,
+    ("vgg16", "pipeline"): 11.0780e9,
+}
+
 
 def bytes_per_element(mode: str, P: int, g: int) -> int:
     """Algorithmic HBM bytes per gradient element for the path a mode runs (g = gradient bytes).
@@ -113,6 +121,9 @@ def main() -> int:
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--blocks-per-cu", type=int, default=0)
     ap.add_argument("--xcd-contiguous", action="store_true")
+    ap.add_argument("--copy-calibration", type=float, default=0.0, metavar="GiB",
+                    help="instead of the benchmark, run a plain device copy of this many GiB `--steps` times "
+                         "(reference dispatch of known size for scaling rocprofv3's FETCH_SIZE / WRITE_SIZE)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (the path is per-GPU; nothing is sharded or "
@@ -130,6 +141,21 @@ def main() -> int:
         print("bench.py: no GPU visible", file=sys.stderr)
         return 2
     torch.cuda.set_device(0)
+
+    if args.copy_calibration > 0:
+        nbytes = int(args.copy_calibration * (1 << 30))
+        src = torch.empty(nbytes // 4, dtype=torch.float32, device="cuda").normal_()
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        ms = (time.perf_counter() - t0) * 1e3 / args.steps
+        print(json.dumps({"calibration": "plain device copy", "bytes_read": nbytes, "bytes_written": nbytes,
+                          "launches": args.steps, "ms_per_copy": round(ms, 4),
+                          "GBps": round(2 * nbytes / ms / 1e6, 1)}))
+        return 0
 
     p = W.make_profile(args.workload)
     n = [int(x) for x in p.n_elems]
@@ -173,7 +199,8 @@ def main() -> int:
         "pct_of_hbm_peak": round(100.0 * value / HBM_PEAK_GBPS, 2),
         "plan_us": round(plan_us, 2),
         "roofline": {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                     "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": None,
+                     "frac": round(achieved / HBM_PEAK_GBPS, 4),
+                     "traffic": MEASURED_TRAFFIC_BYTES.get((args.workload, args.mode)),
                      "kernel": f"mgwfbp_stream_kernel<{args.mode}>", "avg_launch_ms": round(kernel_ms, 5),
                      "algorithmic_bytes_per_launch": step_bytes // nl},
     }

@@ -147,10 +147,11 @@ int mgwfbp_ctx_tables(const mgwfbp_ctx* ctx, int32_t* n_segments, void* tiles_ou
                       uint64_t* seg_off_out, uint32_t* seg_n_out, int32_t* seg_layer_out,
                       int32_t* group_tile_out);
 
-/* Launch shape.  blocks_per_cu <= 0 restores the default; the grid is
- * min(tiles of the call, compute units * blocks_per_cu) workgroups of 256 lanes, each striding
- * over tiles.  xcd_contiguous != 0 renumbers workgroups so that each of the 8 accelerator dies
- * walks one contiguous eighth of the tile range instead of every eighth tile. */
+/* Launch shape.  By default a call launches one workgroup of 256 lanes per tile it covers.
+ * blocks_per_cu > 0 caps the grid at compute units * blocks_per_cu workgroups, which then stride
+ * over the tiles; blocks_per_cu <= 0 restores the default.  xcd_contiguous != 0 renumbers
+ * workgroups so that each of the 8 accelerator dies walks one contiguous eighth of the tile range
+ * instead of every eighth tile. */
 int mgwfbp_ctx_set_launch(mgwfbp_ctx* ctx, int32_t blocks_per_cu, int32_t xcd_contiguous);
 
 /* ---------------------------------------------------------------------------------------------
