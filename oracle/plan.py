@@ -177,6 +177,56 @@ def bruteforce_best(size_bytes, t_backward, a, b) -> Tuple[float, List[int]]:
 
 
 # ------------------------------------------------------------------------------------------
+# the true optimum of the paper's minimisation problem (Eq. 8 minimised over all plans), for any L
+# ------------------------------------------------------------------------------------------
+
+def plan_optimal(size_bytes: Sequence[int], t_backward: Sequence[float], a: float, b: float
+                 ) -> Tuple[float, List[int]]:
+    """Exact minimiser of t_iter - t_f over all 2^(L-1) plans, by dynamic programming over the
+    arrival order.  Not in the paper (its Algorithm 1 is a greedy that Theorem 1 claims optimal; it is
+    not always); the DEFINITION of the result is `bruteforce_best`, which pins this function for L <= 16.
+
+    Let the layers arrive as k = 1..L (k = 1 is layer L).  A plan cuts this sequence into consecutive
+    groups; the group holding arrivals i+1..k sends one message of their summed bytes, starting when
+    arrival k's gradient exists and the previous group's message has ended.  The end time of a group is
+    non-decreasing in the end time of the group before it, so
+        F[0] = 0 ;  F[k] = min over 0 <= i < k of  max(F[i], ready[k]) + (a + b * bytes(i+1..k))
+    and F[L] is the optimum.  Ties take the smallest i (the longest group).  Every candidate is formed
+    with the same operations, in the same order, as `iteration_time` uses for that plan, so F[L] equals
+    `iteration_time(plan)` bit for bit.
+
+    Returns (F[L], merged[0..L-1])."""
+    L = len(size_bytes)
+    if L == 0:
+        return 0.0, []
+    t_b1 = _one_based(float(x) for x in t_backward)
+    tau_b = backward_start_times(t_b1)
+    # arrival k is paper layer L + 1 - k
+    ready = [None] + [tau_b[L + 1 - k] + t_b1[L + 1 - k] for k in range(1, L + 1)]
+    nbytes = [None] + [int(size_bytes[L - k]) for k in range(1, L + 1)]
+    prefix = [0] * (L + 1)
+    for k in range(1, L + 1):
+        prefix[k] = prefix[k - 1] + nbytes[k]
+    F = [0.0] * (L + 1)
+    cut = [0] * (L + 1)
+    for k in range(1, L + 1):
+        best = None
+        for i in range(0, k):
+            start = F[i] if F[i] > ready[k] else ready[k]
+            cand = start + allreduce_time(a, b, prefix[k] - prefix[i])
+            if best is None or cand < best:
+                best, cut[k] = cand, i
+        F[k] = best
+    merged = [MERGED] * L
+    k = L
+    while k > 0:
+        # the group ending at arrival k closes at paper layer L + 1 - k, which is therefore normal
+        merged[(L + 1 - k) - 1] = NORMAL
+        k = cut[k]
+    return F[L], merged
+
+
+# ------------------------------------------------------------------------------------------
 # Algorithm 2 (communication handler): which layers travel together; Sec. 5.3: buffer layout
 # ------------------------------------------------------------------------------------------
 

@@ -348,3 +348,38 @@ def test_plans_of_the_five_profiles_are_valid_and_no_worse_than_wfbp(name):
     t = OP.iteration_time(m, by, tb, p.a, p.b)
     assert t <= OP.wfbp_time(by, tb, p.a, p.b) * (1 + 1e-12)
     assert t >= sum(tb)                                       # cannot end before backpropagation does
+
+
+# ----------------------------------------------------------------------------------------
+# exact optimum (dynamic programme) against its definition: the exhaustive minimum
+# ----------------------------------------------------------------------------------------
+
+def test_plan_optimal_equals_exhaustive_minimum():
+    rng = np.random.default_rng(20)
+    for trial in range(400):
+        L = int(rng.integers(1, 13))
+        by, tb, a, b = _rand_instance(rng, L, size_hi=10 ** 6 if trial % 2 else 5000, allow_empty=True)
+        t_dp, m_dp = OP.plan_optimal(by, tb, a, b)
+        t_bf, _ = OP.bruteforce_best(by, tb, a, b)
+        assert t_dp == t_bf                                         # same operations, same bits
+        assert m_dp[0] == 0
+        assert OP.iteration_time(m_dp, by, tb, a, b) == t_dp        # the returned plan attains it
+
+
+def test_plan_optimal_on_hand_example_and_wide_ranges():
+    t, m = OP.plan_optimal(HAND_BYTES, HAND_TB, 1.0, 1.0)
+    assert m == [0, 1, 0] and t == pytest.approx(102.0)
+    # tie: zero startup and zero slope make every plan end with the backward pass; longest groups win
+    t, m = OP.plan_optimal([4, 4, 4], [1.0, 2.0, 3.0], 0.0, 0.0)
+    assert t == 6.0 and m == [0, 1, 1]
+    rng = np.random.default_rng(21)
+    worse = 0
+    for _ in range(200):
+        L = int(rng.integers(2, 40))
+        by, tb, a, b = _rand_instance(rng, L)
+        t_opt, m_opt = OP.plan_optimal(by, tb, a, b)
+        t_g = OP.iteration_time(OP.plan_algorithm1(by, tb, a, b), by, tb, a, b)
+        assert t_opt <= t_g and t_opt <= OP.wfbp_time(by, tb, a, b) and t_opt <= OP.single_layer_time(by, tb, a, b)
+        assert t_opt >= sum(tb)
+        worse += t_g > t_opt
+    assert worse > 0          # Algorithm 1 really is beaten on some instances
