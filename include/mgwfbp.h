@@ -88,6 +88,18 @@ int mgwfbp_plan(const uint64_t* size_bytes, const double* t_backward_s, int32_t 
                 double a_s, double b_s_per_byte,
                 uint8_t* merged_out, int32_t* group_first_out, int32_t* n_groups_out);
 
+/* The exact minimiser of the paper's objective (Eq. 8 minimised over all plans with layer 1 normal),
+ * which Algorithm 1 approximates: Theorem 1's optimality claim fails on some inputs, e.g. bytes
+ * (0,0,100), t_b (49.1,0.9,0), a = b = 1 gives 102.9 with Algorithm 1 and 102.0 here.  Dynamic
+ * programme over the arrival order, O(L^2) time: the earliest end of the first k arrivals' messages is
+ * min over cuts i of max(end[i], ready[k]) + a + b*bytes(i+1..k).  Ties keep the longest last group.
+ * Arguments as mgwfbp_plan; *t_iter_out (may be NULL) receives the optimum, which equals
+ * mgwfbp_eval of the returned plan bit for bit. */
+int mgwfbp_plan_opt(const uint64_t* size_bytes, const double* t_backward_s, int32_t L,
+                    double a_s, double b_s_per_byte,
+                    uint8_t* merged_out, int32_t* group_first_out, int32_t* n_groups_out,
+                    double* t_iter_out);
+
 /* Iteration time minus forward time, t_iter - t_f, of an arbitrary plan: Eq. 8 evaluated on the
  * timeline of Eq. 6-7 after applying Eq. 12 (no message for a merged layer), Eq. 13 (bytes move
  * down) and Eq. 14 (start of the lower layer).  merged[0] must be 0.  Result in *t_iter_out. */

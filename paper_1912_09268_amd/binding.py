@@ -40,6 +40,7 @@ _vp = C.c_void_p
 
 _SIGNATURES = {
     "mgwfbp_plan": (C.c_int, [_u64p, _f64p, C.c_int32, C.c_double, C.c_double, _u8p, _i32p, _i32p]),
+    "mgwfbp_plan_opt": (C.c_int, [_u64p, _f64p, C.c_int32, C.c_double, C.c_double, _u8p, _i32p, _i32p, _f64p]),
     "mgwfbp_eval": (C.c_int, [_u8p, _u64p, _f64p, C.c_int32, C.c_double, C.c_double, _f64p]),
     "mgwfbp_ctx_create": (C.c_int, [C.POINTER(_vp), _u64p, C.c_int32, _u8p, C.c_int32, C.c_int32]),
     "mgwfbp_ctx_create_host": (C.c_int, [C.POINTER(_vp), _u64p, C.c_int32, _u8p, C.c_int32, C.c_int32]),
@@ -105,6 +106,24 @@ def plan(size_bytes: Sequence[int], t_backward_s: Sequence[float], a_s: float, b
     _check("mgwfbp_plan", lib().mgwfbp_plan(_ptr(sz, _u64p), _ptr(tb, _f64p), L, float(a_s), float(b_s_per_byte),
                                             _ptr(merged, _u8p), _ptr(first, _i32p), C.byref(G)))
     return merged, first[:G.value].copy()
+
+
+def plan_opt(size_bytes: Sequence[int], t_backward_s: Sequence[float], a_s: float, b_s_per_byte: float
+             ) -> Tuple[np.ndarray, np.ndarray, float]:
+    """mgwfbp_plan_opt.  Returns (merged[L] uint8, group_first[G] int32, optimal t_iter - t_f)."""
+    sz = _arr(size_bytes, np.uint64)
+    tb = _arr(t_backward_s, np.float64)
+    L = int(sz.shape[0])
+    if tb.shape[0] != L:
+        raise ValueError("size_bytes and t_backward_s differ in length")
+    merged = np.zeros(L, np.uint8)
+    first = np.zeros(L + 1, np.int32)
+    G = C.c_int32(0)
+    t = C.c_double(0.0)
+    _check("mgwfbp_plan_opt", lib().mgwfbp_plan_opt(_ptr(sz, _u64p), _ptr(tb, _f64p), L, float(a_s),
+                                                    float(b_s_per_byte), _ptr(merged, _u8p), _ptr(first, _i32p),
+                                                    C.byref(G), C.byref(t)))
+    return merged, first[:G.value].copy(), t.value
 
 
 def eval_plan(merged: Sequence[int], size_bytes: Sequence[int], t_backward_s: Sequence[float],

@@ -130,3 +130,59 @@ extern "C" int mgwfbp_eval(const uint8_t* merged, const uint64_t* size_bytes,
     *t_iter_out = finish;
     return MGWFBP_OK;
 }
+
+// Exact minimiser of Eq. 8 over all plans (Algorithm 1 is a greedy and can miss it).
+//
+// Arrival position k = 1..L is tensor L-k.  best_end[k] is the earliest time at which the messages of
+// the first k arrivals can all have ended; the last of them carries arrivals i+1..k for some cut i:
+//     best_end[k] = min_i  max(best_end[i], ready[k]) + (a + b * bytes(i+1..k)),   best_end[0] = 0.
+// The end of a message never gets earlier when the message before it ends later, so taking the
+// minimum at every k is exact.  Ties keep the smallest i.  O(L^2) time, O(L) memory.
+extern "C" int mgwfbp_plan_opt(const uint64_t* size_bytes, const double* t_backward_s, int32_t L,
+                               double a, double b, uint8_t* merged_out, int32_t* group_first_out,
+                               int32_t* n_groups_out, double* t_iter_out) {
+    if (!valid_inputs(size_bytes, t_backward_s, L, a, b)) return MGWFBP_EINVAL;
+    if (L > 0 && merged_out == nullptr) return MGWFBP_EINVAL;
+    if (L == 0) {
+        if (n_groups_out) *n_groups_out = 0;
+        if (group_first_out) group_first_out[0] = -1;
+        if (t_iter_out) *t_iter_out = 0.0;
+        return MGWFBP_OK;
+    }
+    std::vector<double> ready_by_tensor;
+    gradient_ready_times(t_backward_s, L, ready_by_tensor);
+    const size_t n = static_cast<size_t>(L);
+    std::vector<double> best_end(n + 1, 0.0);
+    std::vector<uint64_t> bytes_upto(n + 1, 0);     // bytes of arrivals 1..k
+    std::vector<int32_t> cut(n + 1, 0);
+    for (size_t k = 1; k <= n; ++k) bytes_upto[k] = bytes_upto[k - 1] + size_bytes[n - k];
+    for (size_t k = 1; k <= n; ++k) {
+        const double ready_k = ready_by_tensor[n - k];
+        double best = 0.0;
+        int32_t best_i = -1;
+        for (size_t i = 0; i < k; ++i) {
+            const double start = best_end[i] > ready_k ? best_end[i] : ready_k;
+            const double end = start + message_time(a, b, bytes_upto[k] - bytes_upto[i]);
+            if (best_i < 0 || end < best) {
+                best = end;
+                best_i = static_cast<int32_t>(i);
+            }
+        }
+        best_end[k] = best;
+        cut[k] = best_i;
+    }
+    for (int32_t i = 0; i < L; ++i) merged_out[i] = 1;
+    for (size_t k = n; k > 0; k = static_cast<size_t>(cut[k])) merged_out[n - k] = 0;   // last arrival of a group closes it
+
+    int32_t G = 0;
+    for (int32_t i = L - 1; i >= 0; --i) {
+        if (i == L - 1 || merged_out[i + 1] == 0) {
+            if (group_first_out) group_first_out[G] = i;
+            ++G;
+        }
+    }
+    if (group_first_out) group_first_out[G] = -1;
+    if (n_groups_out) *n_groups_out = G;
+    if (t_iter_out) *t_iter_out = best_end[n];
+    return MGWFBP_OK;
+}

@@ -84,3 +84,48 @@ def test_plan_time_scales_linearly():
     t0 = time.perf_counter()
     M.plan(p.size_bytes, p.t_backward, p.a, p.b)
     assert time.perf_counter() - t0 < 0.5
+
+
+# ----------------------------------------------------------------------------------------
+# mgwfbp_plan_opt: the exact optimum
+# ----------------------------------------------------------------------------------------
+
+def test_plan_opt_matches_oracle_and_exhaustive_search():
+    rng = np.random.default_rng(14)
+    for trial in range(600):
+        L = int(rng.integers(1, 60 if trial % 4 else 12))
+        p = W.make_random_profile(rng, L, size_hi=10 ** 6 if trial % 2 else 5000, allow_empty=True)
+        by, tb = _lists(p)
+        merged, first, t = M.plan_opt(p.size_bytes, p.t_backward, p.a, p.b)
+        t_ref, m_ref = OP.plan_optimal(by, tb, p.a, p.b)
+        assert t == t_ref and merged.tolist() == m_ref                 # bit-exact, same tie-breaking
+        assert M.eval_plan(merged, p.size_bytes, p.t_backward, p.a, p.b) == t
+        assert first.tolist() == [g[0] for g in OP.groups_in_arrival_order(m_ref)]
+        if L <= 11:
+            assert t == OP.bruteforce_best(by, tb, p.a, p.b)[0]        # the definition
+        greedy, _ = M.plan(p.size_bytes, p.t_backward, p.a, p.b)
+        assert t <= M.eval_plan(greedy, p.size_bytes, p.t_backward, p.a, p.b)
+
+
+@pytest.mark.parametrize("name", W.PROFILE_NAMES)
+def test_plan_opt_on_profiles(name, capsys):
+    p = W.make_profile(name)
+    by, tb = _lists(p)
+    merged, first, t = M.plan_opt(p.size_bytes, p.t_backward, p.a, p.b)
+    t_ref, m_ref = OP.plan_optimal(by, tb, p.a, p.b)
+    assert t == t_ref and merged.tolist() == m_ref
+    greedy, gfirst = M.plan(p.size_bytes, p.t_backward, p.a, p.b)
+    t_g = M.eval_plan(greedy, p.size_bytes, p.t_backward, p.a, p.b)
+    assert sum(tb) <= t <= t_g
+    with capsys.disabled():
+        print(f"\n[plan] {name}: Algorithm 1 {len(gfirst)} groups t={t_g * 1e3:.4f} ms | optimum {len(first)} groups "
+              f"t={t * 1e3:.4f} ms | gap {100 * (t_g / t - 1):.4f}% | backward only {sum(tb) * 1e3:.4f} ms")
+
+
+def test_plan_opt_hand_example_and_errors():
+    merged, first, t = M.plan_opt([0, 0, 100], [49.1, 0.9, 0.0], 1.0, 1.0)
+    assert merged.tolist() == [0, 1, 0] and first.tolist() == [2, 1] and t == pytest.approx(102.0)
+    merged, first, t = M.plan_opt([], [], 1.0, 1.0)
+    assert merged.size == 0 and first.size == 0 and t == 0.0
+    with pytest.raises(M.MgwfbpError):
+        M.plan_opt([4, 4], [1.0, float("nan")], 1.0, 1.0)
