@@ -186,6 +186,15 @@ int mgwfbp_ctx_set_launch(mgwfbp_ctx* ctx, int32_t blocks_per_cu, int32_t xcd_co
 int mgwfbp_pack(mgwfbp_ctx* ctx, int32_t group, const void* const* d_grad_ptrs,
                 void* const* d_merge_bufs, void* hip_stream);
 
+/* Algorithm 2, communication handler (`lb.push(l)`): as gradients arrive, copy the tensors
+ * first_tensor, first_tensor-1, ..., last_tensor (a run in arrival order, first_tensor >= last_tensor;
+ * it may cross group boundaries) of all P workers into their places in the merge arenas.  Covering every
+ * tensor of a group with such calls, in any order and any split into runs, leaves the group's slices
+ * exactly as mgwfbp_pack(group) does; the group's buffer is "full" (Sec. 5.3) once its lowest tensor,
+ * the one with merged[i] = 0, has been packed.  Errors: MGWFBP_EINVAL for an empty or out-of-range run. */
+int mgwfbp_pack_tensors(mgwfbp_ctx* ctx, int32_t first_tensor, int32_t last_tensor,
+                        const void* const* d_grad_ptrs, void* const* d_merge_bufs, void* hip_stream);
+
 /* Eq. 2, aggregation part: d_reduced[j] = (sum over w in order of merge[w][j]) * (1/P) for every
  * element j of the group's slice. */
 int mgwfbp_reduce(mgwfbp_ctx* ctx, int32_t group, const void* const* d_merge_bufs,

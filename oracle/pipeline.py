@@ -67,6 +67,30 @@ def pack(grads: Sequence[np.ndarray], groups: Sequence[Sequence[int]]) -> List[n
     return buffers
 
 
+def pack_as_gradients_arrive(grads: Sequence[np.ndarray], merged: Sequence[int]):
+    """Algorithm 2's communication handler for one worker, one iteration: layers are popped in the order
+    L, L-1, ..., 1; each is pushed to the layer buffer (its gradient is copied behind what the buffer
+    already holds, Sec. 5.3), and when the pushed layer is a normal layer the buffer is full: it is
+    handed to the all-reduce and a fresh buffer is started.
+
+    Returns the list of full buffers in the order they were handed over, each with the 0-based tensor
+    indices it holds: [(buffer, [indices]), ...]."""
+    L = len(grads)
+    sent = []
+    parts: List[np.ndarray] = []
+    members: List[int] = []
+    for l in range(L, 0, -1):
+        parts.append(grads[l - 1])            # lb.push(l)
+        members.append(l - 1)
+        if merged[l - 1] == 0:                # m[l] == l_n
+            buf = np.concatenate(parts) if parts else np.empty(0, grads[0].dtype)
+            sent.append((buf, members))
+            parts, members = [], []
+    if parts:
+        raise ValueError("layer 1 must be a normal layer")
+    return sent
+
+
 # ------------------------------------------------------------------------------------------
 # reduce
 # ------------------------------------------------------------------------------------------

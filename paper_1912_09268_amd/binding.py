@@ -50,6 +50,7 @@ _SIGNATURES = {
     "mgwfbp_ctx_tables": (C.c_int, [_vp, _i32p, _vp, _u64p, _u32p, _i32p, _i32p]),
     "mgwfbp_ctx_set_launch": (C.c_int, [_vp, C.c_int32, C.c_int32]),
     "mgwfbp_pack": (C.c_int, [_vp, C.c_int32, _vp, _vp, _vp]),
+    "mgwfbp_pack_tensors": (C.c_int, [_vp, C.c_int32, C.c_int32, _vp, _vp, _vp]),
     "mgwfbp_reduce": (C.c_int, [_vp, C.c_int32, _vp, _vp, _vp]),
     "mgwfbp_unpack_update": (C.c_int, [_vp, C.c_int32, _vp, _vp, _vp, C.c_float, C.c_float, _vp]),
     "mgwfbp_reduce_update": (C.c_int, [_vp, C.c_int32, _vp, _vp, _vp, C.c_float, C.c_float, _vp]),
@@ -211,6 +212,11 @@ class Context:
     # ---- device calls: addresses are plain integers ---------------------------------------
     def pack(self, group: int, d_grad_ptrs: int, d_merge_bufs: int, stream: int = 0) -> None:
         _check("mgwfbp_pack", lib().mgwfbp_pack(self._h, int(group), _vp(d_grad_ptrs), _vp(d_merge_bufs), _vp(stream)))
+
+    def pack_tensors(self, first_tensor: int, last_tensor: int, d_grad_ptrs: int, d_merge_bufs: int,
+                     stream: int = 0) -> None:
+        _check("mgwfbp_pack_tensors", lib().mgwfbp_pack_tensors(self._h, int(first_tensor), int(last_tensor),
+                                                                _vp(d_grad_ptrs), _vp(d_merge_bufs), _vp(stream)))
 
     def reduce(self, group: int, d_merge_bufs: int, d_reduced: int, stream: int = 0) -> None:
         _check("mgwfbp_reduce", lib().mgwfbp_reduce(self._h, int(group), _vp(d_merge_bufs), _vp(d_reduced), _vp(stream)))

@@ -132,6 +132,8 @@ template <typename GradT> struct Args {
     int32_t L, P;
     int32_t tile_first, tile_count;
     int32_t xcd_contiguous;
+    int32_t clipped;                 // 0: whole tiles; 1: only arena elements in [clip_lo, clip_hi)
+    int64_t clip_lo, clip_hi;
 };
 
 // Pointers of the P workers, either held in registers (P known at compile time) or re-read from the
@@ -319,15 +321,18 @@ __device__ __forceinline__ int block_inclusive_scan(int x, int* s_wave) {
 
 template <int KIND, typename GradT, int PT>
 __device__ void general_tile(const Args<GradT>& A, const WorkerPtrs<GradT, PT>& mrg, const TileHdr& h,
-                             int64_t tile_base, int* s_loc, int* s_layer, int* s_wave) {
+                             int64_t tile_base, int clo, int chi, int* s_loc, int* s_layer, int* s_wave) {
+    // Only tile-local elements [clo, chi) are touched; 0 <= clo < chi <= h.valid.
     const int tid = threadIdx.x;
     const int valid = h.valid;
+    const int p_first = (clo & ~(VEC - 1)) + tid * VEC;
     if constexpr (!needs_owner(KIND)) {
-        for (int p = tid * VEC; p < valid; p += BLOCK * VEC) {
-            if (p + VEC <= valid) {
+        for (int p = p_first; p < chi; p += BLOCK * VEC) {
+            if (p >= clo && p + VEC <= chi) {
                 do_one<KIND, GradT, PT, VEC>(A, mrg, 0, 0, tile_base + p);
             } else {
-                for (int q = p; q < valid; ++q) do_one<KIND, GradT, PT, 1>(A, mrg, 0, 0, tile_base + q);
+                const int q_end = min(p + VEC, chi);
+                for (int q = max(p, clo); q < q_end; ++q) do_one<KIND, GradT, PT, 1>(A, mrg, 0, 0, tile_base + q);
             }
         }
         return;
@@ -355,19 +360,21 @@ __device__ void general_tile(const Args<GradT>& A, const WorkerPtrs<GradT, PT>& 
         };
         auto end_of = [&](int j) -> int { return (j + 1 < nseg) ? start_of(j + 1) : valid; };
         auto layer_of = [&](int j) -> int { return staged ? s_layer[j] : ro(A.seg_layer)[h.seg0 + j]; };
-        for (int p = tid * VEC; p < valid; p += BLOCK * VEC) {
-            int lo = 0, hi = nseg - 1;          // owner of p: last j with start_of(j) <= p (segment 0 starts <= 0)
+        for (int p = p_first; p < chi; p += BLOCK * VEC) {
+            const int q0 = max(p, clo);         // first element of this vector that is wanted
+            int lo = 0, hi = nseg - 1;          // its owner: last j with start_of(j) <= q0 (segment 0 starts <= 0)
             while (lo < hi) {
                 const int mid = (lo + hi + 1) >> 1;
-                if (start_of(mid) <= p) lo = mid; else hi = mid - 1;
+                if (start_of(mid) <= q0) lo = mid; else hi = mid - 1;
             }
             int j = lo;
-            if (p + VEC <= end_of(j)) {
+            if (p >= clo && p + VEC <= min(end_of(j), chi)) {
                 const int64_t soff = (j == 0) ? (static_cast<int64_t>(p) - h.first_start)
                                               : static_cast<int64_t>(p - start_of(j));
                 do_one<KIND, GradT, PT, VEC>(A, mrg, layer_of(j), soff, tile_base + p);
             } else {
-                for (int q = p; q < p + VEC && q < valid; ++q) {
+                const int q_end = min(p + VEC, chi);
+                for (int q = q0; q < q_end; ++q) {
                     while (j + 1 < nseg && q >= start_of(j + 1)) ++j;
                     const int64_t soff = (j == 0) ? (static_cast<int64_t>(q) - h.first_start)
                                                   : static_cast<int64_t>(q - start_of(j));
@@ -426,10 +433,17 @@ __global__ void __launch_bounds__(MGWFBP_BLOCK) mgwfbp_stream_kernel(const Args<
         const int tile = A.tile_first + t;
         const TileHdr h = load_header(A.tiles + tile);
         const int64_t tile_base = static_cast<int64_t>(tile) * TILE;
-        if (h.valid == TILE && (!needs_owner(KIND) || h.nseg == 1)) {
+        int clo = 0, chi = h.valid;
+        if (A.clipped) {                        // uniform over the workgroup
+            const int64_t l = A.clip_lo - tile_base, u = A.clip_hi - tile_base;
+            if (l > 0) clo = l < h.valid ? static_cast<int>(l) : h.valid;
+            if (u < h.valid) chi = u > 0 ? static_cast<int>(u) : 0;
+            if (chi <= clo) continue;
+        }
+        if (clo == 0 && chi == TILE && (!needs_owner(KIND) || h.nseg == 1)) {
             fast_tile<KIND, GradT, PT>(A, mrg, h.layer0, -h.first_start, tile_base);
         } else {
-            general_tile<KIND, GradT, PT>(A, mrg, h, tile_base, s_loc, s_layer, s_wave);
+            general_tile<KIND, GradT, PT>(A, mrg, h, tile_base, clo, chi, s_loc, s_layer, s_wave);
         }
     }
 }
@@ -540,18 +554,29 @@ int launch_by_p(const Args<GradT>& A, int grid, hipStream_t stream) {
     }
 }
 
+// Tile range and element clip of one call: either a group (or all groups), or an arena interval.
+struct Span {
+    int32_t t0 = 0, t1 = 0;
+    bool clipped = false;
+    int64_t lo = 0, hi = 0;
+};
+
 template <int KIND>
 int run(mgwfbp_ctx* c, int32_t group, const void* const* grad_ptrs, void* const* merge_bufs, float* reduced,
-        float* const* w_ptrs, float* const* v_ptrs, float lr, float mu, void* stream_v) {
+        float* const* w_ptrs, float* const* v_ptrs, float lr, float mu, void* stream_v,
+        const Span* span = nullptr) {
     if (c == nullptr || !c->on_device) return MGWFBP_EINVAL;
-    if (group < -1 || group >= c->host.G) return MGWFBP_EINVAL;
+    if (span == nullptr && (group < -1 || group >= c->host.G)) return MGWFBP_EINVAL;
     if (reads_grads(KIND) && grad_ptrs == nullptr) return MGWFBP_EINVAL;
     if ((reads_merge(KIND) || writes_merge(KIND)) && merge_bufs == nullptr) return MGWFBP_EINVAL;
     if ((KIND == K_REDUCE || KIND == K_UPDATE) && reduced == nullptr) return MGWFBP_EINVAL;
     if (updates(KIND) && (w_ptrs == nullptr || v_ptrs == nullptr)) return MGWFBP_EINVAL;
 
     int32_t t0, t1;
-    if (group < 0) {
+    if (span != nullptr) {
+        t0 = span->t0;
+        t1 = span->t1;
+    } else if (group < 0) {
         t0 = 0;
         t1 = static_cast<int32_t>(c->host.tiles.size());
     } else {
@@ -576,18 +601,22 @@ int run(mgwfbp_ctx* c, int32_t group, const void* const* grad_ptrs, void* const*
     }
     hipStream_t stream = static_cast<hipStream_t>(stream_v);
     const float inv_p = 1.0f / static_cast<float>(c->P);
+    const int32_t clip_on = (span != nullptr && span->clipped) ? 1 : 0;
+    const int64_t clip_lo = span ? span->lo : 0, clip_hi = span ? span->hi : 0;
 
     if (c->dtype == MGWFBP_F32) {
         Args<float> A{c->d_tiles, c->d_seg_n, c->d_seg_layer, c->d_seg_off,
                       reinterpret_cast<const float* const*>(grad_ptrs),
                       reinterpret_cast<float* const*>(merge_bufs), reduced, w_ptrs, v_ptrs,
-                      lr, mu, inv_p, c->host.L, c->P, t0, count, xcd};
+                      lr, mu, inv_p, c->host.L, c->P, t0, count, xcd,
+                      clip_on, clip_lo, clip_hi};
         return launch_by_p<KIND, float>(A, grid, stream);
     }
     Args<uint16_t> A{c->d_tiles, c->d_seg_n, c->d_seg_layer, c->d_seg_off,
                      reinterpret_cast<const uint16_t* const*>(grad_ptrs),
                      reinterpret_cast<uint16_t* const*>(merge_bufs), reduced, w_ptrs, v_ptrs,
-                     lr, mu, inv_p, c->host.L, c->P, t0, count, xcd};
+                     lr, mu, inv_p, c->host.L, c->P, t0, count, xcd,
+                     clip_on, clip_lo, clip_hi};
     return launch_by_p<KIND, uint16_t>(A, grid, stream);
 }
 
@@ -662,6 +691,31 @@ int mgwfbp_ctx_set_launch(mgwfbp_ctx* c, int32_t blocks_per_cu, int32_t xcd_cont
 int mgwfbp_pack(mgwfbp_ctx* c, int32_t group, const void* const* d_grad_ptrs, void* const* d_merge_bufs,
                 void* hip_stream) {
     return run<K_PACK>(c, group, d_grad_ptrs, d_merge_bufs, nullptr, nullptr, nullptr, 0.f, 0.f, hip_stream);
+}
+
+int mgwfbp_pack_tensors(mgwfbp_ctx* c, int32_t first_tensor, int32_t last_tensor, const void* const* d_grad_ptrs,
+                        void* const* d_merge_bufs, void* hip_stream) {
+    if (c == nullptr || !c->on_device) return MGWFBP_EINVAL;
+    const HostTables& h = c->host;
+    if (last_tensor < 0 || first_tensor >= h.L || first_tensor < last_tensor) return MGWFBP_EINVAL;
+    // Tensors lie in the arena in arrival order, so the run first_tensor, ..., last_tensor occupies one
+    // arena interval (group padding inside it belongs to no tile's valid part and is skipped).
+    uint64_t lo = UINT64_MAX, hi = 0;
+    for (int32_t i = first_tensor; i >= last_tensor; --i) {
+        const size_t q = static_cast<size_t>(i);
+        if (h.tensor_n[q] == 0) continue;
+        const uint64_t start = h.group_base[static_cast<size_t>(h.tensor_group[q])] + h.tensor_off[q];
+        if (start < lo) lo = start;
+        if (start + h.tensor_n[q] > hi) hi = start + h.tensor_n[q];
+    }
+    if (hi <= lo) return MGWFBP_OK;                               // only empty tensors
+    Span s;
+    s.t0 = static_cast<int32_t>(lo / TILE);
+    s.t1 = static_cast<int32_t>((hi + TILE - 1) / TILE);
+    s.clipped = true;
+    s.lo = static_cast<int64_t>(lo);
+    s.hi = static_cast<int64_t>(hi);
+    return run<K_PACK>(c, 0, d_grad_ptrs, d_merge_bufs, nullptr, nullptr, nullptr, 0.f, 0.f, hip_stream, &s);
 }
 
 int mgwfbp_reduce(mgwfbp_ctx* c, int32_t group, const void* const* d_merge_bufs, float* d_reduced,

@@ -28,6 +28,7 @@ int mgwfbp_build_tables(const uint64_t* n_elems, int32_t L, const uint8_t* merge
         out.L = L;
         out.tensor_off.assign(static_cast<size_t>(L), 0);
         out.tensor_group.assign(static_cast<size_t>(L), 0);
+        out.tensor_n.assign(n_elems, n_elems + L);
         out.group_tile.push_back(0);
         uint64_t next_tile = 0;                        // first free tile of the arena
         int32_t i = L - 1;

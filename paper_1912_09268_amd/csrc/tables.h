@@ -42,6 +42,7 @@ struct HostTables {
     // per tensor
     std::vector<uint64_t> tensor_off;     // [L] element offset inside the group's slice
     std::vector<int32_t> tensor_group;    // [L]
+    std::vector<uint64_t> tensor_n;       // [L] element count
     // per group (arrival order)
     std::vector<uint64_t> group_base;     // [G] arena element
     std::vector<uint64_t> group_elems;    // [G]

@@ -121,6 +121,10 @@ class DeviceModel:
     def pack(self, group: int = -1) -> None:
         self.ctx.pack(group, self.grad_ptrs.data_ptr(), self.merge_ptrs.data_ptr(), self._stream())
 
+    def pack_tensors(self, first_tensor: int, last_tensor: int) -> None:
+        self.ctx.pack_tensors(first_tensor, last_tensor, self.grad_ptrs.data_ptr(), self.merge_ptrs.data_ptr(),
+                              self._stream())
+
     def reduce(self, group: int = -1) -> None:
         self.ctx.reduce(group, self.merge_ptrs.data_ptr(), self.reduced.data_ptr(), self._stream())
 

@@ -249,3 +249,102 @@ def test_device_entry_points_reject_bad_arguments():
 def test_full_size_profiles(name, mode):
     p = W.make_profile(name)
     check_case(p, _plan_of(p), mode, steps=1)
+
+
+# ------------------------------------------------------------------------------------------
+# arrival-driven packing (Algorithm 2's handler): tensor by tensor, and in random runs
+# ------------------------------------------------------------------------------------------
+
+def _check_incremental(profile, merged, splitter, misalign=0, label=""):
+    import torch
+    import paper_1912_09268_amd as M
+    from paper_1912_09268_amd import harness as H
+    _say(f"[incremental] {label or profile.name} L={profile.L} E={profile.total_elems} P={profile.P} {profile.grad_dtype}")
+    n = [int(x) for x in profile.n_elems]
+    merged = [int(x) for x in merged]
+    ctx = M.Context(n, merged, profile.P, M.BF16 if profile.grad_dtype == "bf16" else M.F32)
+    dm = H.DeviceModel(ctx, n, misalign=misalign, fill_arena=True)
+    off, grp, base, ge = ctx.layout()
+    flats = [W.worker_gradient_flat(profile, w) for w in range(profile.P)]
+    for w in range(profile.P):
+        dm.upload_grads(w, flats[w])
+    w_flat, v_flat = W.initial_weights_flat(profile), W.initial_momentum_flat(profile)
+    dm.upload_weights(w_flat, v_flat)
+    grads = [W.split_by_layer(f, profile.n_elems) for f in flats]
+    # device: push runs of tensors as they "arrive"; when a run contains a group's normal layer the
+    # group's buffer is full -> reduce + update that group
+    L = profile.L
+    hi = L - 1
+    closed = 0
+    for run_len in splitter(L):
+        lo = max(hi - run_len + 1, 0)
+        dm.pack_tensors(hi, lo)
+        while closed < ctx.n_groups and all(grp[i] != closed or i >= lo for i in range(L)):
+            dm.reduce(closed)
+            dm.unpack_update(profile.lr, profile.momentum, closed)
+            closed += 1
+        hi = lo - 1
+        if hi < 0:
+            break
+    assert closed == ctx.n_groups
+    torch.cuda.synchronize()
+    # oracle: the handler's buffers, in the order they fill
+    sent = [OD.pack_as_gradients_arrive(grads[w], merged) for w in range(profile.P)]
+    w_o = [x.copy() for x in W.split_by_layer(w_flat, profile.n_elems)]
+    v_o = [x.copy() for x in W.split_by_layer(v_flat, profile.n_elems)]
+    merge_dev = [dm.download_merge(w) for w in range(profile.P)]
+    red_dev = dm.download_reduced()
+    covered = np.zeros(max(ctx.arena_elems, 1), bool)
+    groups, reduced = [], []
+    for k in range(ctx.n_groups):
+        lo_e, hi_e = int(base[k]), int(base[k]) + int(ge[k])
+        covered[lo_e:hi_e] = True
+        bufs = [sent[w][k][0] for w in range(profile.P)]
+        for w in range(profile.P):
+            assert np.array_equal(_bits(merge_dev[w][lo_e:hi_e]), _bits(bufs[w])), f"merge w={w} group={k}"
+        r = OD.reduce_average(bufs)
+        assert np.array_equal(_bits(red_dev[lo_e:hi_e]), _bits(r))
+        groups.append(sent[0][k][1])
+        reduced.append(r)
+    for w in range(profile.P):
+        m = _bits(merge_dev[w])
+        assert (m[~covered] == (H.SENTINEL32 if m.dtype == np.uint32 else H.SENTINEL16)).all()
+    OD.unpack_update(reduced, groups, w_o, v_o, profile.lr, profile.momentum)
+    assert np.array_equal(_bits(dm.download_weights()), _bits(np.concatenate(w_o)))
+    assert np.array_equal(_bits(dm.download_momenta()), _bits(np.concatenate(v_o)))
+    ctx.close()
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_pack_tensor_by_tensor_as_gradients_arrive(dtype):
+    rng = np.random.default_rng(31)
+    p = W.make_random_profile(rng, 70, size_lo=1, size_hi=12000, P=4, grad_dtype=dtype, allow_empty=True)
+    merged = [0] + [int(x) for x in (rng.random(p.L - 1) < 0.6)]
+    _check_incremental(p, merged, lambda L: [1] * L, label="one tensor per call")
+    _check_incremental(p, merged, lambda L: [1] * L, misalign=5, label="one tensor per call, misaligned")
+    _check_incremental(p, merged, lambda L: [int(x) for x in np.random.default_rng(5).integers(1, 9, size=L)],
+                       label="random runs")
+    _check_incremental(p, merged, lambda L: [L], label="everything in one run")
+
+
+def test_pack_tensors_on_toy_and_tiny_profiles():
+    p = W.make_profile("toy_mlp")
+    _check_incremental(p, _plan_of(p), lambda L: [1] * L)
+    rng = np.random.default_rng(32)
+    sizes = [1] * 700 + [3, 1, 2, 5] * 40 + [9000]
+    q = W.Profile("ones", np.asarray(sizes, np.uint64), rng.uniform(1e-6, 1e-5, len(sizes)), 1e-4, 1e-9, 2, "f32", 1.0)
+    merged = [0] + [int(x) for x in (rng.random(len(sizes) - 1) < 0.95)]
+    _check_incremental(q, merged, lambda L: [int(x) for x in np.random.default_rng(6).integers(1, 40, size=L)],
+                       label="many one-element tensors")
+
+
+def test_pack_tensors_rejects_bad_runs():
+    import paper_1912_09268_amd as M
+    from paper_1912_09268_amd import harness as H
+    ctx = M.Context([100, 0, 100], [0, 1, 1], 2, M.F32)
+    dm = H.DeviceModel(ctx, [100, 0, 100])
+    for first, last in ((0, 1), (3, 0), (1, -1)):
+        with pytest.raises(M.MgwfbpError):
+            dm.pack_tensors(first, last)
+    dm.pack_tensors(1, 1)            # an empty tensor: accepted, nothing to do
+    ctx.close()

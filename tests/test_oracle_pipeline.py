@@ -222,3 +222,22 @@ def test_merged_step_tiny_case_by_hand():
     assert reduced[0].tolist() == [2.0, 4.0, 2.0]
     assert v[1].tolist() == [4.0] and v[0].tolist() == [4.5, 1.0]          # 0.5*v + g
     assert w[1].tolist() == [-1.0] and w[0].tolist() == [-1.25, 0.5]       # w - 0.5*v
+
+
+def test_arrival_driven_pack_equals_whole_group_pack():
+    rng = np.random.default_rng(9)
+    for _ in range(30):
+        L = int(rng.integers(1, 40))
+        n = rng.integers(0, 200, size=L)
+        grads = [rng.integers(0, 1000, size=int(k)).astype(np.float32) for k in n]
+        m = [0] + [int(x) for x in rng.integers(0, 2, size=L - 1)]
+        groups = OP.groups_in_arrival_order(m)
+        sent = OD.pack_as_gradients_arrive(grads, m)
+        bufs = OD.pack(grads, groups)
+        assert [idx for _, idx in sent] == groups
+        for (buf, _), ref in zip(sent, bufs):
+            assert np.array_equal(buf, ref)
+    # by hand: layers 3,2 merged into 1 -> one buffer [g3 | g2 | g1]
+    g = [np.array([1.0], np.float32), np.array([2.0, 3.0], np.float32), np.array([4.0], np.float32)]
+    (buf, idx), = OD.pack_as_gradients_arrive(g, [0, 1, 1])
+    assert buf.tolist() == [4.0, 2.0, 3.0, 1.0] and idx == [2, 1, 0]
