@@ -107,6 +107,40 @@ int mgwfbp_eval(const uint8_t* merged, const uint64_t* size_bytes, const double*
                 int32_t L, double a_s, double b_s_per_byte, double* t_iter_out);
 
 /* ---------------------------------------------------------------------------------------------
+ * Host: where a and b come from, and the worker-count sweep
+ * ------------------------------------------------------------------------------------------- */
+
+typedef enum mgwfbp_allreduce_algorithm {   /* rows of Table 2 */
+    MGWFBP_AR_BINARY_TREE = 0,              /* a = 2 alpha log N      b = (2 beta + gamma) log N                 */
+    MGWFBP_AR_RECURSIVE_DOUBLING = 1,       /* a = alpha log N        b = (beta + gamma) log N                   */
+    MGWFBP_AR_HALVING_DOUBLING = 2,         /* a = 2 alpha log N      b = 2 beta - (2 beta + gamma)/N + gamma    */
+    MGWFBP_AR_DOUBLE_BINARY_TREES = 3,      /* a = 2 alpha log N      b = beta + gamma   (the table prints the
+                                               startup without alpha; read as for the other rows)               */
+    MGWFBP_AR_RING = 4                      /* a = 2 (N-1) alpha      b = 2 (N-1)/N beta + (N-1)/N gamma         */
+} mgwfbp_allreduce_algorithm;
+
+/* Table 2: all-reduce startup a and per-byte cost b from the point-to-point latency alpha (s), the
+ * per-byte transfer time beta (s/B), the per-byte summation time gamma (s/B) and the worker count N >= 1.
+ * log is base 2.  Errors: MGWFBP_EINVAL (unknown algorithm, N < 1, negative or non-finite input). */
+int mgwfbp_allreduce_ab(int32_t algorithm, int32_t n_workers, double alpha_s, double beta_s_per_byte,
+                        double gamma_s_per_byte, double* a_out, double* b_out);
+
+/* Sec. 6.2 (Fig. 4): a and b as the least-squares line through n >= 2 measured (message bytes, seconds)
+ * points with at least two different sizes. */
+int mgwfbp_fit_ab(const uint64_t* message_bytes, const double* seconds, int32_t n,
+                  double* a_out, double* b_out);
+
+/* Sec. 6.4: for every worker count, take (a, b) from Table 2 and report the iteration time
+ * (t_forward_s + Eq. 8) of wait-free backpropagation (every layer normal), of single-layer
+ * communication (everything merged, Eq. 9) and of MG-WFBP (Algorithm 1), plus the number of messages
+ * MG-WFBP sends.  Any out array (host, [n_counts]) may be NULL.  The speedup over one worker is
+ * N * (t_forward_s + sum t_backward_s) / t_iter. */
+int mgwfbp_simulate(const uint64_t* size_bytes, const double* t_backward_s, int32_t L, double t_forward_s,
+                    int32_t algorithm, double alpha_s, double beta_s_per_byte, double gamma_s_per_byte,
+                    const int32_t* worker_counts, int32_t n_counts,
+                    double* t_wfbp_out, double* t_single_out, double* t_mgwfbp_out, int32_t* groups_out);
+
+/* ---------------------------------------------------------------------------------------------
  * Host: context = group/offset table for one (tensor sizes, plan, P, dtype), uploaded once
  * ------------------------------------------------------------------------------------------- */
 

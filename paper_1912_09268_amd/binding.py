@@ -42,6 +42,10 @@ _SIGNATURES = {
     "mgwfbp_plan": (C.c_int, [_u64p, _f64p, C.c_int32, C.c_double, C.c_double, _u8p, _i32p, _i32p]),
     "mgwfbp_plan_opt": (C.c_int, [_u64p, _f64p, C.c_int32, C.c_double, C.c_double, _u8p, _i32p, _i32p, _f64p]),
     "mgwfbp_eval": (C.c_int, [_u8p, _u64p, _f64p, C.c_int32, C.c_double, C.c_double, _f64p]),
+    "mgwfbp_allreduce_ab": (C.c_int, [C.c_int32, C.c_int32, C.c_double, C.c_double, C.c_double, _f64p, _f64p]),
+    "mgwfbp_fit_ab": (C.c_int, [_u64p, _f64p, C.c_int32, _f64p, _f64p]),
+    "mgwfbp_simulate": (C.c_int, [_u64p, _f64p, C.c_int32, C.c_double, C.c_int32, C.c_double, C.c_double, C.c_double,
+                                  _i32p, C.c_int32, _f64p, _f64p, _f64p, _i32p]),
     "mgwfbp_ctx_create": (C.c_int, [C.POINTER(_vp), _u64p, C.c_int32, _u8p, C.c_int32, C.c_int32]),
     "mgwfbp_ctx_create_host": (C.c_int, [C.POINTER(_vp), _u64p, C.c_int32, _u8p, C.c_int32, C.c_int32]),
     "mgwfbp_ctx_destroy": (None, [_vp]),
@@ -137,6 +141,46 @@ def eval_plan(merged: Sequence[int], size_bytes: Sequence[int], t_backward_s: Se
     _check("mgwfbp_eval", lib().mgwfbp_eval(_ptr(m, _u8p), _ptr(sz, _u64p), _ptr(tb, _f64p), int(sz.shape[0]),
                                             float(a_s), float(b_s_per_byte), C.byref(out)))
     return out.value
+
+
+AR_BINARY_TREE, AR_RECURSIVE_DOUBLING, AR_HALVING_DOUBLING, AR_DOUBLE_BINARY_TREES, AR_RING = range(5)
+
+
+def allreduce_ab(algorithm: int, n_workers: int, alpha_s: float, beta_s_per_byte: float, gamma_s_per_byte: float
+                 ) -> Tuple[float, float]:
+    """mgwfbp_allreduce_ab -> (a, b)."""
+    a, b = C.c_double(), C.c_double()
+    _check("mgwfbp_allreduce_ab", lib().mgwfbp_allreduce_ab(int(algorithm), int(n_workers), float(alpha_s),
+                                                            float(beta_s_per_byte), float(gamma_s_per_byte),
+                                                            C.byref(a), C.byref(b)))
+    return a.value, b.value
+
+
+def fit_ab(message_bytes: Sequence[int], seconds: Sequence[float]) -> Tuple[float, float]:
+    """mgwfbp_fit_ab -> (a, b)."""
+    m = _arr(message_bytes, np.uint64)
+    t = _arr(seconds, np.float64)
+    if m.shape[0] != t.shape[0]:
+        raise ValueError("message_bytes and seconds differ in length")
+    a, b = C.c_double(), C.c_double()
+    _check("mgwfbp_fit_ab", lib().mgwfbp_fit_ab(_ptr(m, _u64p), _ptr(t, _f64p), int(m.shape[0]), C.byref(a), C.byref(b)))
+    return a.value, b.value
+
+
+def simulate(size_bytes: Sequence[int], t_backward_s: Sequence[float], t_forward_s: float, algorithm: int,
+             alpha_s: float, beta_s_per_byte: float, gamma_s_per_byte: float, worker_counts: Sequence[int]):
+    """mgwfbp_simulate -> (t_wfbp[n], t_single[n], t_mgwfbp[n], groups[n])."""
+    sz = _arr(size_bytes, np.uint64)
+    tb = _arr(t_backward_s, np.float64)
+    wc = _arr(worker_counts, np.int32)
+    n = int(wc.shape[0])
+    tw, ts, tm = np.zeros(n), np.zeros(n), np.zeros(n)
+    g = np.zeros(n, np.int32)
+    _check("mgwfbp_simulate", lib().mgwfbp_simulate(
+        _ptr(sz, _u64p), _ptr(tb, _f64p), int(sz.shape[0]), float(t_forward_s), int(algorithm), float(alpha_s),
+        float(beta_s_per_byte), float(gamma_s_per_byte), _ptr(wc, _i32p), n, _ptr(tw, _f64p), _ptr(ts, _f64p),
+        _ptr(tm, _f64p), _ptr(g, _i32p)))
+    return tw, ts, tm, g
 
 
 # --------------------------------------------------------------------------------------------
