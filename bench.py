@@ -36,6 +36,7 @@ MEASURED_TRAFFIC_BYTES = {
 def bytes_per_element(mode: str, P: int, g: int) -> int:
     """Algorithmic HBM bytes per gradient element for the path a mode runs (g = gradient bytes).
     pack 2*P*g | reduce P*g + 4 | unpack_update 20 | fused forms drop the intermediate traffic."""
+    mode = mode[:-len("_graph")] if mode.endswith("_graph") else mode
     if mode in ("pipeline", "pipeline_per_group"):
         return 2 * P * g + 16            # read P grads, write P merge, read+write w and v
     if mode == "reduce_update":
@@ -46,6 +47,7 @@ def bytes_per_element(mode: str, P: int, g: int) -> int:
 
 
 def launches_per_step(mode: str, G: int) -> int:
+    mode = mode[:-len("_graph")] if mode.endswith("_graph") else mode
     return {"pipeline": 1, "pipeline_per_group": G, "reduce_update": 2, "staged": 3, "staged_per_group": 3 * G}[mode]
 
 
@@ -68,17 +70,29 @@ def run_step(dm, mode: str, lr: float, mu: float, G: int) -> None:
 
 def time_mode(dm, mode, lr, mu, G, steps, warmup):
     """Returns (wall ms per step, HIP-event ms per step).  Events sit on torch's current stream, which
-    is the stream handed to the library."""
+    is the stream handed to the library.  A mode ending in `_graph` captures one step of the base mode
+    into a HIP graph once and replays it."""
     import torch
+    if mode.endswith("_graph"):
+        base = mode[:-len("_graph")]
+        run_step(dm, base, lr, mu, G)            # warm up outside capture
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            run_step(dm, base, lr, mu, G)
+        step = graph.replay
+    else:
+        def step():
+            run_step(dm, mode, lr, mu, G)
     for _ in range(warmup):
-        run_step(dm, mode, lr, mu, G)
+        step()
     torch.cuda.synchronize()
     e0 = torch.cuda.Event(enable_timing=True)
     e1 = torch.cuda.Event(enable_timing=True)
     t0 = time.perf_counter()
     e0.record()
     for _ in range(steps):
-        run_step(dm, mode, lr, mu, G)
+        step()
     e1.record()
     torch.cuda.synchronize()
     wall = (time.perf_counter() - t0) * 1e3 / steps
@@ -116,7 +130,8 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="resnet50")
     ap.add_argument("--mode", default="pipeline",
-                    choices=["pipeline", "pipeline_per_group", "reduce_update", "staged", "staged_per_group"])
+                    choices=["pipeline", "pipeline_per_group", "reduce_update", "staged", "staged_per_group",
+                             "pipeline_per_group_graph", "staged_per_group_graph"])
     ap.add_argument("--all-modes", action="store_true", help="also time the other launch modes (extra keys)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--blocks-per-cu", type=int, default=0)
@@ -206,10 +221,11 @@ def main() -> int:
     }
     if args.all_modes:
         others = {}
-        for mode in ("pipeline", "pipeline_per_group", "reduce_update", "staged", "staged_per_group"):
+        for mode in ("pipeline", "pipeline_per_group", "pipeline_per_group_graph", "reduce_update", "staged",
+                     "staged_per_group", "staged_per_group_graph"):
             if mode == args.mode:
                 continue
-            k = max(10, args.steps // (4 if mode.endswith("per_group") else 1))
+            k = max(10, args.steps // (4 if "per_group" in mode else 1))
             wl, ev = time_mode(dm, mode, p.lr, p.momentum, G, k, max(2, args.warmup // 4))
             b = bytes_per_element(mode, p.P, g) * E
             others[mode] = {"ms_per_step": round(wl, 5), "GBps": round(b / (wl * 1e-3) / 1e9, 1),

@@ -348,3 +348,44 @@ def test_pack_tensors_rejects_bad_runs():
             dm.pack_tensors(first, last)
     dm.pack_tensors(1, 1)            # an empty tensor: accepted, nothing to do
     ctx.close()
+
+
+# ------------------------------------------------------------------------------------------
+# HIP graph: one launch per group captured once, replayed with eager work in between
+# ------------------------------------------------------------------------------------------
+
+def test_per_group_launches_replay_correctly_from_a_hip_graph():
+    import torch
+    import paper_1912_09268_amd as M
+    from paper_1912_09268_amd import harness as H
+    p = W.make_profile("toy_mlp")
+    rng = np.random.default_rng(40)
+    q = W.make_random_profile(rng, 40, size_hi=15000, P=8)
+    for prof, merged in ((p, _plan_of(p)), (q, [0] + [int(x) for x in (rng.random(q.L - 1) < 0.5)])):
+        n = [int(x) for x in prof.n_elems]
+        ctx = M.Context(n, merged, prof.P, M.F32)
+        dm = H.DeviceModel(ctx, n, fill_arena=True)
+        flats = [W.worker_gradient_flat(prof, w) for w in range(prof.P)]
+        for w in range(prof.P):
+            dm.upload_grads(w, flats[w])
+        w_flat, v_flat = W.initial_weights_flat(prof), W.initial_momentum_flat(prof)
+        dm.upload_weights(w_flat, v_flat)
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):                      # capture only: nothing runs here
+            for k in range(ctx.n_groups):
+                dm.group_pipeline(prof.lr, prof.momentum, k)
+        grads = [W.split_by_layer(f, prof.n_elems) for f in flats]
+        groups = OP.groups_in_arrival_order(merged)
+        w_o = [x.copy() for x in W.split_by_layer(w_flat, prof.n_elems)]
+        v_o = [x.copy() for x in W.split_by_layer(v_flat, prof.n_elems)]
+        scratch = torch.zeros(1 << 20, device="cuda")
+        for replay in range(4):
+            graph.replay()
+            scratch.add_(1.0)                              # the program's own eager work between replays
+            torch.cuda.synchronize()
+            OD.merged_step(grads, groups, w_o, v_o, prof.lr, prof.momentum)
+            assert np.array_equal(_bits(dm.download_weights()), _bits(np.concatenate(w_o))), f"replay {replay}"
+            assert np.array_equal(_bits(dm.download_momenta()), _bits(np.concatenate(v_o))), f"replay {replay}"
+        assert float(scratch[0]) == 4.0
+        ctx.close()
