@@ -389,3 +389,66 @@ def test_per_group_launches_replay_correctly_from_a_hip_graph():
             assert np.array_equal(_bits(dm.download_momenta()), _bits(np.concatenate(v_o))), f"replay {replay}"
         assert float(scratch[0]) == 4.0
         ctx.close()
+
+
+# ------------------------------------------------------------------------------------------
+# maximum sizes: a tensor with more than 2^31 elements (64-bit offsets everywhere)
+# ------------------------------------------------------------------------------------------
+
+def test_tensor_with_more_than_two_to_the_31_elements():
+    """Inputs are drawn on the device with torch's seeded generator (not by the library); the oracle
+    recomputes windows of the result element by element from downloaded windows of those inputs."""
+    import torch
+    import paper_1912_09268_amd as M
+    from paper_1912_09268_amd import harness as H
+    big = 2 ** 31 + 10007
+    n = [3001, big, 17]
+    merged = [0, 1, 1]                      # one group: tensor 2 at offset 0, the big tensor at 17, tensor 0 behind it
+    P = 2
+    _say(f"[parity] huge tensor: {big} bf16 elements, P={P}")
+    ctx = M.Context(n, merged, P, M.BF16)
+    off, grp, base, ge = ctx.layout()
+    assert off.tolist() == [17 + big, 17, 0] and int(ge[0]) == sum(n)
+    dm = H.DeviceModel(ctx, n, fill_arena=True)
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(1912)
+    for w in range(P):
+        for t in dm.grads[w]:
+            t.random_(0x3A00, 0x3C00, generator=gen)          # bfloat16 patterns of small positive values
+            t[::2].neg_()                                       # flip the sign bit of every other one... of the int16
+    for t in dm.w:
+        t.normal_(generator=gen)
+    for t in dm.v:
+        t.normal_(0.0, 1e-2, generator=gen)
+    torch.cuda.synchronize()
+
+    def window(t, lo, hi):
+        a = t[lo:hi].cpu().numpy()
+        return a.view(np.uint16) if a.dtype == np.int16 else a
+
+    # windows inside the big tensor (start, around 2^31 elements and 2^32 bytes, end) and the small tensors
+    spans = {1: [(0, 6000), (2 ** 30 - 3000, 2 ** 30 + 3000), (2 ** 31 - 3000, 2 ** 31 + 3000), (big - 6000, big)],
+             0: [(0, 3001)], 2: [(0, 17)]}
+    before = {}
+    for i, lst in spans.items():
+        for lo, hi in lst:
+            before[(i, lo)] = ([window(dm.grads[w][i], lo, hi) for w in range(P)],
+                               window(dm.w[i], lo, hi).copy(), window(dm.v[i], lo, hi).copy())
+    dm.group_pipeline(0.1, 0.9)
+    torch.cuda.synchronize()
+    for i, lst in spans.items():
+        for lo, hi in lst:
+            g, w0, v0 = before[(i, lo)]
+            a_lo = int(base[0]) + int(off[i]) + lo
+            for w in range(P):
+                assert np.array_equal(window(dm.merge[w], a_lo, a_lo + hi - lo), g[w]), (i, lo, w)
+            r = OD.reduce_average(g)
+            assert np.array_equal(_bits(window(dm.reduced, a_lo, a_lo + hi - lo)), _bits(r)), (i, lo)
+            OD.sgd_momentum(w0, v0, r, 0.1, 0.9)
+            assert np.array_equal(_bits(window(dm.v[i], lo, hi)), _bits(v0)), (i, lo)
+            assert np.array_equal(_bits(window(dm.w[i], lo, hi)), _bits(w0)), (i, lo)
+    # the padding behind the group is untouched
+    end = int(base[0]) + int(ge[0])
+    tail = window(dm.merge[0], end, ctx.arena_elems)
+    assert (tail == H.SENTINEL16).all()
+    ctx.close()
