@@ -136,6 +136,9 @@ def main() -> int:
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--blocks-per-cu", type=int, default=0)
     ap.add_argument("--xcd-contiguous", action="store_true")
+    ap.add_argument("--tiles-per-workgroup", type=int, default=0)
+    ap.add_argument("--resident-mib", type=int, default=-1,
+                    help="MiB of w+v kept cacheable (library default if negative)")
     ap.add_argument("--copy-calibration", type=float, default=0.0, metavar="GiB",
                     help="instead of the benchmark, run a plain device copy of this many GiB `--steps` times "
                          "(reference dispatch of known size for scaling rocprofv3's FETCH_SIZE / WRITE_SIZE)")
@@ -186,7 +189,9 @@ def main() -> int:
     G = int(first.shape[0])
 
     ctx = M.Context(n, merged, p.P, M.BF16 if p.grad_dtype == "bf16" else M.F32)
-    ctx.set_launch(args.blocks_per_cu, args.xcd_contiguous)
+    ctx.set_launch(args.blocks_per_cu, args.xcd_contiguous, args.tiles_per_workgroup)
+    if args.resident_mib >= 0:
+        ctx.set_resident_bytes(args.resident_mib << 20)
     dm = H.DeviceModel(ctx, n)
     for w in range(p.P):
         dm.upload_grads(w, W.worker_gradient_flat(p, w))

@@ -193,12 +193,22 @@ int mgwfbp_ctx_tables(const mgwfbp_ctx* ctx, int32_t* n_segments, void* tiles_ou
                       uint64_t* seg_off_out, uint32_t* seg_n_out, int32_t* seg_layer_out,
                       int32_t* group_tile_out);
 
-/* Launch shape.  By default a call launches one workgroup of 256 lanes per tile it covers.
- * blocks_per_cu > 0 caps the grid at compute units * blocks_per_cu workgroups, which then stride
- * over the tiles; blocks_per_cu <= 0 restores the default.  xcd_contiguous != 0 renumbers
- * workgroups so that each of the 8 accelerator dies walks one contiguous eighth of the tile range
- * instead of every eighth tile. */
-int mgwfbp_ctx_set_launch(mgwfbp_ctx* ctx, int32_t blocks_per_cu, int32_t xcd_contiguous);
+/* Launch shape.  By default a call launches one workgroup of 256 lanes per tile it covers (per 16 KiB of
+ * each worker's data for mgwfbp_pack, which runs as P single-worker copies).
+ *   blocks_per_cu > 0        caps the grid at compute units * blocks_per_cu workgroups, which then stride
+ *                            over the work; <= 0 restores the default
+ *   xcd_contiguous != 0      renumbers workgroups so that each of the 8 accelerator dies walks one
+ *                            contiguous eighth of the range instead of every eighth piece
+ *   tiles_per_workgroup > 0  consecutive tiles a workgroup handles per turn; <= 0 restores the default */
+int mgwfbp_ctx_set_launch(mgwfbp_ctx* ctx, int32_t blocks_per_cu, int32_t xcd_contiguous,
+                          int32_t tiles_per_workgroup);
+
+/* How many bytes of weights + momenta (8 per element, counted from the start of the arena) are accessed
+ * with ordinary loads and stores so that they stay in the GPU's 256 MB memory-side cache from one
+ * iteration to the next; the rest of w and v is streamed with non-temporal accesses like the gradients.
+ * Results do not depend on it.  Default 232 MiB; 0 streams everything.  Synchronous (re-uploads the tile
+ * table); do not call while kernels of this context are in flight. */
+int mgwfbp_ctx_set_resident_bytes(mgwfbp_ctx* ctx, uint64_t bytes);
 
 /* ---------------------------------------------------------------------------------------------
  * Device: the pipeline.  `group` is a group number 0..G-1, or -1 for every group in one launch.

@@ -52,7 +52,8 @@ _SIGNATURES = {
     "mgwfbp_ctx_dims": (C.c_int, [_vp, _i32p, _i32p, _i32p, _i32p, _u64p, _i32p, _i32p]),
     "mgwfbp_ctx_layout": (C.c_int, [_vp, _u64p, _i32p, _u64p, _u64p]),
     "mgwfbp_ctx_tables": (C.c_int, [_vp, _i32p, _vp, _u64p, _u32p, _i32p, _i32p]),
-    "mgwfbp_ctx_set_launch": (C.c_int, [_vp, C.c_int32, C.c_int32]),
+    "mgwfbp_ctx_set_launch": (C.c_int, [_vp, C.c_int32, C.c_int32, C.c_int32]),
+    "mgwfbp_ctx_set_resident_bytes": (C.c_int, [_vp, C.c_uint64]),
     "mgwfbp_pack": (C.c_int, [_vp, C.c_int32, _vp, _vp, _vp]),
     "mgwfbp_pack_tensors": (C.c_int, [_vp, C.c_int32, C.c_int32, _vp, _vp, _vp]),
     "mgwfbp_reduce": (C.c_int, [_vp, C.c_int32, _vp, _vp, _vp]),
@@ -250,8 +251,12 @@ class Context:
         return {"tiles": tiles, "seg_off": seg_off, "seg_n": seg_n, "seg_layer": seg_layer,
                 "group_tile": group_tile}
 
-    def set_launch(self, blocks_per_cu: int = 0, xcd_contiguous: bool = False) -> None:
-        _check("mgwfbp_ctx_set_launch", lib().mgwfbp_ctx_set_launch(self._h, int(blocks_per_cu), int(bool(xcd_contiguous))))
+    def set_launch(self, blocks_per_cu: int = 0, xcd_contiguous: bool = False, tiles_per_workgroup: int = 0) -> None:
+        _check("mgwfbp_ctx_set_launch", lib().mgwfbp_ctx_set_launch(self._h, int(blocks_per_cu), int(bool(xcd_contiguous)),
+                                                                    int(tiles_per_workgroup)))
+
+    def set_resident_bytes(self, nbytes: int) -> None:
+        _check("mgwfbp_ctx_set_resident_bytes", lib().mgwfbp_ctx_set_resident_bytes(self._h, int(nbytes)))
 
     # ---- device calls: addresses are plain integers ---------------------------------------
     def pack(self, group: int, d_grad_ptrs: int, d_merge_bufs: int, stream: int = 0) -> None:

@@ -32,6 +32,7 @@
 // -ffp-contract=off so that mu*v + g and w - lr*v are never fused.
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
 #include <cstdint>
 #include <cstring>
 #include <new>
@@ -132,25 +133,36 @@ template <typename GradT> struct Args {
     int32_t L, P;
     int32_t tile_first, tile_count;
     int32_t xcd_contiguous;
+    int32_t tiles_per_wg;            // consecutive tiles one workgroup handles per turn, >= 1
+    int32_t n_units;                 // ceil(tile_count / tiles_per_wg)
+    int32_t worker_split;            // 1: gridDim.y = P and every workgroup serves worker blockIdx.y alone
     int32_t clipped;                 // 0: whole tiles; 1: only arena elements in [clip_lo, clip_hi)
     int64_t clip_lo, clip_hi;
 };
+
+// First worker a workgroup serves.  PACK has no arithmetic across workers, so it is launched as P
+// single-worker copies side by side in gridDim.y: workgroups are dispatched x-fastest, the chip then
+// streams one worker's gradients at a time (2 streams instead of 2P), which the memory system serves
+// faster.
+template <typename GradT> __device__ __forceinline__ int worker_base(const Args<GradT>& A) {
+    return A.worker_split ? static_cast<int>(blockIdx.y) : 0;
+}
 
 // Pointers of the P workers, either held in registers (P known at compile time) or re-read from the
 // table on every use (any P).
 template <typename T, int PT> struct WorkerPtrs {
     T* p[PT];
-    __device__ __forceinline__ void fetch(T* const* table, int64_t stride, int64_t index, int) {
+    __device__ __forceinline__ void fetch(T* const* table, int64_t stride, int64_t index, int w0) {
 #pragma unroll
-        for (int w = 0; w < PT; ++w) p[w] = ro(table)[w * stride + index];
+        for (int w = 0; w < PT; ++w) p[w] = ro(table)[(w0 + w) * stride + index];
     }
     __device__ __forceinline__ T* get(int w) const { return p[w]; }
 };
 template <typename T> struct WorkerPtrs<T, 0> {
     T* const* base;
     int64_t stride;
-    __device__ __forceinline__ void fetch(T* const* table, int64_t s, int64_t index, int) {
-        base = table + index;
+    __device__ __forceinline__ void fetch(T* const* table, int64_t s, int64_t index, int w0) {
+        base = table + w0 * s + index;
         stride = s;
     }
     __device__ __forceinline__ T* get(int w) const { return ro(base)[w * stride]; }
@@ -166,7 +178,7 @@ template <typename GradT, int PT, int W> struct Regs {
 // load phase / store phase for one vector or element at arena position `apos`, which is element
 // `soff` of its tensor
 // ---------------------------------------------------------------------------------------------
-template <int KIND, typename GradT, int PT, int W>
+template <int KIND, typename GradT, int PT, int W, bool WVNT>
 __device__ __forceinline__ void load_phase(Regs<GradT, PT, W>& R, const Args<GradT>& A,
                                            const WorkerPtrs<const GradT, PT>& src,
                                            const WorkerPtrs<GradT, PT>& mrg,
@@ -184,12 +196,12 @@ __device__ __forceinline__ void load_phase(Regs<GradT, PT, W>& R, const Args<Gra
     }
     if constexpr (KIND == K_UPDATE) R.r = ld<NT_LD, FV>(A.reduced + apos);
     if constexpr (updates(KIND)) {
-        R.w = ld<NT_WV, FV>(wp + soff);
-        R.v = ld<NT_WV, FV>(vp + soff);
+        R.w = ld<WVNT, FV>(wp + soff);
+        R.v = ld<WVNT, FV>(vp + soff);
     }
 }
 
-template <int KIND, typename GradT, int PT, int W>
+template <int KIND, typename GradT, int PT, int W, bool WVNT>
 __device__ __forceinline__ void store_phase(Regs<GradT, PT, W>& R, const Args<GradT>& A,
                                             const WorkerPtrs<const GradT, PT>& src,
                                             const WorkerPtrs<GradT, PT>& mrg,
@@ -246,8 +258,8 @@ __device__ __forceinline__ void store_phase(Regs<GradT, PT, W>& R, const Args<Gr
             setc(vn, c, v1);
             setc(wn, c, w1);
         }
-        st<NT_WV, FV>(vp + soff, vn);
-        st<NT_WV, FV>(wp + soff, wn);
+        st<WVNT, FV>(vp + soff, vn);
+        st<WVNT, FV>(wp + soff, wn);
     }
 }
 
@@ -258,26 +270,26 @@ __device__ __forceinline__ void do_one(const Args<GradT>& A, const WorkerPtrs<Gr
     WorkerPtrs<const GradT, PT> src;
     float* wp = nullptr;
     float* vp = nullptr;
-    if constexpr (reads_grads(KIND)) src.fetch(A.grad_ptrs, A.L, layer, 0);
+    if constexpr (reads_grads(KIND)) src.fetch(A.grad_ptrs, A.L, layer, worker_base(A));
     if constexpr (updates(KIND)) {
         wp = ro(A.w_ptrs)[layer];
         vp = ro(A.v_ptrs)[layer];
     }
     Regs<GradT, PT, W> R;
-    load_phase<KIND, GradT, PT, W>(R, A, src, mrg, wp, vp, soff, apos);
-    store_phase<KIND, GradT, PT, W>(R, A, src, mrg, wp, vp, soff, apos);
+    load_phase<KIND, GradT, PT, W, NT_WV>(R, A, src, mrg, wp, vp, soff, apos);
+    store_phase<KIND, GradT, PT, W, NT_WV>(R, A, src, mrg, wp, vp, soff, apos);
 }
 
 // ---------------------------------------------------------------------------------------------
 // fast path: the whole tile belongs to one tensor
 // ---------------------------------------------------------------------------------------------
-template <int KIND, typename GradT, int PT>
+template <int KIND, typename GradT, int PT, bool WVNT>
 __device__ __forceinline__ void fast_tile(const Args<GradT>& A, const WorkerPtrs<GradT, PT>& mrg,
                                           int layer, int64_t tensor_off, int64_t tile_base) {
     WorkerPtrs<const GradT, PT> src;
     float* wp = nullptr;
     float* vp = nullptr;
-    if constexpr (reads_grads(KIND)) src.fetch(A.grad_ptrs, A.L, layer, 0);
+    if constexpr (reads_grads(KIND)) src.fetch(A.grad_ptrs, A.L, layer, worker_base(A));
     if constexpr (updates(KIND)) {
         wp = ro(A.w_ptrs)[layer];
         vp = ro(A.v_ptrs)[layer];
@@ -287,12 +299,12 @@ __device__ __forceinline__ void fast_tile(const Args<GradT>& A, const WorkerPtrs
 #pragma unroll
     for (int u = 0; u < TVECS; ++u) {
         const int p = u * (BLOCK * VEC) + lane_elem;
-        load_phase<KIND, GradT, PT, VEC>(R[u], A, src, mrg, wp, vp, tensor_off + p, tile_base + p);
+        load_phase<KIND, GradT, PT, VEC, WVNT>(R[u], A, src, mrg, wp, vp, tensor_off + p, tile_base + p);
     }
 #pragma unroll
     for (int u = 0; u < TVECS; ++u) {
         const int p = u * (BLOCK * VEC) + lane_elem;
-        store_phase<KIND, GradT, PT, VEC>(R[u], A, src, mrg, wp, vp, tensor_off + p, tile_base + p);
+        store_phase<KIND, GradT, PT, VEC, WVNT>(R[u], A, src, mrg, wp, vp, tensor_off + p, tile_base + p);
     }
 }
 
@@ -413,23 +425,27 @@ __global__ void __launch_bounds__(MGWFBP_BLOCK) mgwfbp_stream_kernel(const Args<
     __shared__ int s_wave[BLOCK / 64];
 
     WorkerPtrs<GradT, PT> mrg;
-    if constexpr (reads_merge(KIND) || writes_merge(KIND)) mrg.fetch(A.merge_bufs, 1, 0, 0);
+    if constexpr (reads_merge(KIND) || writes_merge(KIND)) mrg.fetch(A.merge_bufs, 1, 0, worker_base(A));
 
-    int t_begin, t_end, t_step;
+    // Work is dealt in units of `tiles_per_wg` consecutive tiles.
+    const int K = A.tiles_per_wg;
+    const int n_units = A.n_units;              // ceil(tile_count / K), computed on the host
+    int u_begin, u_end, u_step;
     if (A.xcd_contiguous) {
         // workgroup ids are dealt round-robin to the 8 dies: die = id % 8.  Give each die one
-        // contiguous eighth of the tiles.
+        // contiguous eighth of the units.
         const int die = blockIdx.x & 7;
-        const int per_die = (A.tile_count + 7) >> 3;
-        t_begin = die * per_die + static_cast<int>(blockIdx.x >> 3);
-        t_end = min(A.tile_count, (die + 1) * per_die);
-        t_step = static_cast<int>(gridDim.x >> 3);
+        const int per_die = (n_units + 7) >> 3;
+        u_begin = die * per_die + static_cast<int>(blockIdx.x >> 3);
+        u_end = min(n_units, (die + 1) * per_die);
+        u_step = static_cast<int>(gridDim.x >> 3);
     } else {
-        t_begin = blockIdx.x;
-        t_end = A.tile_count;
-        t_step = gridDim.x;
+        u_begin = blockIdx.x;
+        u_end = n_units;
+        u_step = gridDim.x;
     }
-    for (int t = t_begin; t < t_end; t += t_step) {
+    for (int u = u_begin; u < u_end; u += u_step)
+    for (int t = u * K; t < min((u + 1) * K, A.tile_count); ++t) {
         const int tile = A.tile_first + t;
         const TileHdr h = load_header(A.tiles + tile);
         const int64_t tile_base = static_cast<int64_t>(tile) * TILE;
@@ -441,7 +457,19 @@ __global__ void __launch_bounds__(MGWFBP_BLOCK) mgwfbp_stream_kernel(const Args<
             if (chi <= clo) continue;
         }
         if (clo == 0 && chi == TILE && (!needs_owner(KIND) || h.nseg == 1)) {
-            fast_tile<KIND, GradT, PT>(A, mrg, h.layer0, -h.first_start, tile_base);
+            // Tiles flagged "resident" keep their w and v in the memory-side cache between iterations
+            // (ordinary loads and stores); all other w, v traffic is streamed past it like the gradients.
+            // The two arms differ only in the cache policy of their memory instructions; the empty asm
+            // statements keep the optimiser from merging them back into one (which drops the policy).
+            if (!updates(KIND) || (h.reserved & 1)) {
+                asm volatile("; w and v cacheable" ::: "memory");
+                fast_tile<KIND, GradT, PT, NT_WV>(A, mrg, h.layer0, -h.first_start, tile_base);
+                asm volatile("; end w and v cacheable" ::: "memory");
+            } else {
+                asm volatile("; w and v streamed" ::: "memory");
+                fast_tile<KIND, GradT, PT, true>(A, mrg, h.layer0, -h.first_start, tile_base);
+                asm volatile("; end w and v streamed" ::: "memory");
+            }
         } else {
             general_tile<KIND, GradT, PT>(A, mrg, h, tile_base, clo, chi, s_loc, s_layer, s_wave);
         }
@@ -470,6 +498,8 @@ struct mgwfbp_ctx {
     int n_cu = 0;
     int32_t blocks_per_cu = 0;
     int32_t xcd_contiguous = 0;
+    int32_t tiles_per_wg = 0;         // 0 = per-kernel default
+    uint64_t resident_bytes = 0;      // budget of w + v bytes kept cacheable
     // device copies
     TileHdr* d_tiles = nullptr;
     uint32_t* d_seg_n = nullptr;
@@ -483,6 +513,23 @@ namespace {
 // chip's accesses to each of the 2P+2 streams inside a narrow moving window; measured faster than a
 // persistent grid for every profile.
 constexpr int32_t DEFAULT_BLOCKS_PER_CU = 0;
+
+// Default share of the 256 MB memory-side cache given to weights and momenta.
+constexpr uint64_t DEFAULT_RESIDENT_BYTES = 232ull << 20;
+
+// Marks the leading tiles whose w + v bytes (8 per element) fit into the budget.
+void mark_resident_tiles(HostTables& h, uint64_t budget) {
+    uint64_t used = 0;
+    for (TileHdr& t : h.tiles) {
+        const uint64_t need = static_cast<uint64_t>(t.valid) * 8u;
+        if (used + need <= budget) {
+            t.reserved = 1;
+            used += need;
+        } else {
+            t.reserved = 0;
+        }
+    }
+}
 
 template <typename T> int upload(T** dst, const std::vector<T>& src) {
     const size_t bytes = (src.empty() ? 1 : src.size()) * sizeof(T);
@@ -512,6 +559,8 @@ int create_common(mgwfbp_ctx** out, const uint64_t* n_elems, int32_t L, const ui
     c->P = P;
     c->dtype = dtype;
     c->blocks_per_cu = DEFAULT_BLOCKS_PER_CU;
+    c->resident_bytes = DEFAULT_RESIDENT_BYTES;
+    mark_resident_tiles(c->host, c->resident_bytes);
     if (device) {
         hipDeviceProp_t prop;
         rc = note(hipGetDevice(&c->device));
@@ -534,8 +583,8 @@ int create_common(mgwfbp_ctx** out, const uint64_t* n_elems, int32_t L, const ui
 }
 
 template <int KIND, typename GradT, int PT>
-int launch_one(const Args<GradT>& A, int grid, hipStream_t stream) {
-    hipLaunchKernelGGL((mgwfbp_stream_kernel<KIND, GradT, PT>), dim3(grid), dim3(BLOCK), 0, stream, A);
+int launch_one(const Args<GradT>& A, int grid, hipStream_t stream, int grid_y = 1) {
+    hipLaunchKernelGGL((mgwfbp_stream_kernel<KIND, GradT, PT>), dim3(grid, grid_y), dim3(BLOCK), 0, stream, A);
     return note(hipGetLastError());
 }
 
@@ -543,6 +592,10 @@ template <int KIND, typename GradT>
 int launch_by_p(const Args<GradT>& A, int grid, hipStream_t stream) {
     if constexpr (KIND == K_UPDATE) {
         return launch_one<KIND, GradT, 0>(A, grid, stream);   // no per-worker data
+    } else if constexpr (KIND == K_PACK) {
+        Args<GradT> B = A;                                     // P independent single-worker copies
+        B.worker_split = 1;
+        return launch_one<KIND, GradT, 1>(B, grid, stream, A.P);
     } else {
         switch (A.P) {
             case 2: return launch_one<KIND, GradT, 2>(A, grid, stream);
@@ -591,8 +644,13 @@ int run(mgwfbp_ctx* c, int32_t group, const void* const* grad_ptrs, void* const*
     if (rc != MGWFBP_OK) return rc;
     if (dev != c->device) return MGWFBP_EINVAL;   // tables live on the device the context was made on
 
-    int grid = count;
-    if (c->blocks_per_cu > 0 && static_cast<int64_t>(c->n_cu) * c->blocks_per_cu < count)
+    // tiles per workgroup: PACK runs as single-worker copies, whose tiles are small (one stream in, one
+    // out), so it takes several tiles per workgroup to keep the dispatcher from being the limit
+    int32_t tpw = c->tiles_per_wg;
+    if (tpw <= 0) tpw = (KIND == K_PACK) ? std::max(1, 16384 / (TILE * (c->dtype == MGWFBP_F32 ? 4 : 2))) : 1;
+    const int32_t units = (count + tpw - 1) / tpw;
+    int grid = units;
+    if (c->blocks_per_cu > 0 && static_cast<int64_t>(c->n_cu) * c->blocks_per_cu < units)
         grid = c->n_cu * c->blocks_per_cu;
     int32_t xcd = 0;
     if (c->xcd_contiguous && grid >= 64) {
@@ -608,14 +666,14 @@ int run(mgwfbp_ctx* c, int32_t group, const void* const* grad_ptrs, void* const*
         Args<float> A{c->d_tiles, c->d_seg_n, c->d_seg_layer, c->d_seg_off,
                       reinterpret_cast<const float* const*>(grad_ptrs),
                       reinterpret_cast<float* const*>(merge_bufs), reduced, w_ptrs, v_ptrs,
-                      lr, mu, inv_p, c->host.L, c->P, t0, count, xcd,
+                      lr, mu, inv_p, c->host.L, c->P, t0, count, xcd, tpw, units, 0,
                       clip_on, clip_lo, clip_hi};
         return launch_by_p<KIND, float>(A, grid, stream);
     }
     Args<uint16_t> A{c->d_tiles, c->d_seg_n, c->d_seg_layer, c->d_seg_off,
                      reinterpret_cast<const uint16_t* const*>(grad_ptrs),
                      reinterpret_cast<uint16_t* const*>(merge_bufs), reduced, w_ptrs, v_ptrs,
-                     lr, mu, inv_p, c->host.L, c->P, t0, count, xcd,
+                     lr, mu, inv_p, c->host.L, c->P, t0, count, xcd, tpw, units, 0,
                      clip_on, clip_lo, clip_hi};
     return launch_by_p<KIND, uint16_t>(A, grid, stream);
 }
@@ -681,10 +739,21 @@ int mgwfbp_ctx_tables(const mgwfbp_ctx* c, int32_t* n_segments, void* tiles_out,
     return MGWFBP_OK;
 }
 
-int mgwfbp_ctx_set_launch(mgwfbp_ctx* c, int32_t blocks_per_cu, int32_t xcd_contiguous) {
-    if (c == nullptr || blocks_per_cu > 4096) return MGWFBP_EINVAL;
+int mgwfbp_ctx_set_launch(mgwfbp_ctx* c, int32_t blocks_per_cu, int32_t xcd_contiguous, int32_t tiles_per_workgroup) {
+    if (c == nullptr || blocks_per_cu > 4096 || tiles_per_workgroup > 1024) return MGWFBP_EINVAL;
+    c->tiles_per_wg = tiles_per_workgroup <= 0 ? 0 : tiles_per_workgroup;
     c->blocks_per_cu = blocks_per_cu <= 0 ? DEFAULT_BLOCKS_PER_CU : blocks_per_cu;
     c->xcd_contiguous = xcd_contiguous ? 1 : 0;
+    return MGWFBP_OK;
+}
+
+int mgwfbp_ctx_set_resident_bytes(mgwfbp_ctx* c, uint64_t bytes) {
+    if (c == nullptr) return MGWFBP_EINVAL;
+    c->resident_bytes = bytes;
+    mark_resident_tiles(c->host, bytes);
+    if (c->on_device && !c->host.tiles.empty())
+        return note(hipMemcpy(c->d_tiles, c->host.tiles.data(), c->host.tiles.size() * sizeof(TileHdr),
+                              hipMemcpyHostToDevice));
     return MGWFBP_OK;
 }
 
