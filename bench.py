@@ -99,6 +99,21 @@ def time_mode(dm, mode, lr, mu, G, steps, warmup):
     return wall, e0.elapsed_time(e1) / steps
 
 
+def autotune_launch(ctx, dm, mode, lr, mu, G, blocks_per_cu, xcd, candidates=(1, 2, 4), steps=8):
+    """Pick tiles-per-workgroup by timing real steps.  Results do not depend on the launch shape (every
+    element is computed by the same instruction sequence whatever workgroup handles it), so a training
+    loop can do the same during its first iterations at no cost."""
+    best, best_ms, seen = candidates[0], None, {}
+    for k in candidates:
+        ctx.set_launch(blocks_per_cu, xcd, k)
+        _, ms = time_mode(dm, mode, lr, mu, G, steps, 2)
+        seen[k] = round(ms, 5)
+        if best_ms is None or ms < best_ms * 0.995:      # prefer the earlier candidate on a tie
+            best, best_ms = k, ms
+    ctx.set_launch(blocks_per_cu, xcd, best)
+    return best, seen
+
+
 def cpu_baseline(profile, merged, bytes_per_step, budget_s=10.0):
     """The oracle as it stands, timed on this host for whole steps until `budget_s` is used up."""
     import numpy as np
@@ -136,7 +151,9 @@ def main() -> int:
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--blocks-per-cu", type=int, default=0)
     ap.add_argument("--xcd-contiguous", action="store_true")
-    ap.add_argument("--tiles-per-workgroup", type=int, default=0)
+    ap.add_argument("--tiles-per-workgroup", type=int, default=-1,
+                    help="consecutive tiles per workgroup; 0 = library default, negative = pick 1, 2 or 4 by "
+                         "timing a few untimed steps first")
     ap.add_argument("--resident-mib", type=int, default=-1,
                     help="MiB of w+v kept cacheable (library default if negative)")
     ap.add_argument("--copy-calibration", type=float, default=0.0, metavar="GiB",
@@ -189,7 +206,7 @@ def main() -> int:
     G = int(first.shape[0])
 
     ctx = M.Context(n, merged, p.P, M.BF16 if p.grad_dtype == "bf16" else M.F32)
-    ctx.set_launch(args.blocks_per_cu, args.xcd_contiguous, args.tiles_per_workgroup)
+    ctx.set_launch(args.blocks_per_cu, args.xcd_contiguous, max(args.tiles_per_workgroup, 0))
     if args.resident_mib >= 0:
         ctx.set_resident_bytes(args.resident_mib << 20)
     dm = H.DeviceModel(ctx, n)
@@ -199,6 +216,11 @@ def main() -> int:
     torch.cuda.synchronize()
 
     E = p.total_elems
+    tuned = None
+    if args.tiles_per_workgroup < 0 and "per_group" not in args.mode:
+        tpw, tuned = autotune_launch(ctx, dm, args.mode, p.lr, p.momentum, G, args.blocks_per_cu, args.xcd_contiguous)
+    else:
+        tpw = max(args.tiles_per_workgroup, 0)
     wall_ms, event_ms = time_mode(dm, args.mode, p.lr, p.momentum, G, args.steps, args.warmup)
     bpe = bytes_per_element(args.mode, p.P, g)
     step_bytes = bpe * E
@@ -215,7 +237,8 @@ def main() -> int:
         "config": {"workload": args.workload, "tensors": p.L, "elements": E, "groups": G, "P": p.P,
                    "mode": args.mode, "launches_per_step": nl, "bytes_per_element": bpe,
                    "tile_elems": ctx.tile_elems, "blocks_per_cu": args.blocks_per_cu or "default",
-                   "xcd_contiguous": bool(args.xcd_contiguous)},
+                   "xcd_contiguous": bool(args.xcd_contiguous),
+                   "tiles_per_workgroup": tpw or "default", "autotune_ms": tuned},
         "pct_of_hbm_peak": round(100.0 * value / HBM_PEAK_GBPS, 2),
         "plan_us": round(plan_us, 2),
         "roofline": {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
