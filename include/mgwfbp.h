@@ -184,7 +184,7 @@ int mgwfbp_ctx_layout(const mgwfbp_ctx* ctx, uint64_t* tensor_off, int32_t* tens
  *                  first segment minus the tile's own start, <= 0), int32 first_end (tile-local end
  *                  of that segment), int32 seg0 (its number), int32 nseg (segments intersecting the
  *                  tile), int32 valid (leading elements of the tile inside the group), int32 layer0
- *                  (tensor index of seg0), int32 reserved
+ *                  (tensor index of seg0), int32 flags (bit 0: w and v of the tile use ordinary, cacheable accesses)
  *   seg_off_out    host [S+1]  arena element where each segment starts; [S] = arena_elems
  *   seg_n_out      host [S]    elements of each segment, saturated at 2^32-1
  *   seg_layer_out  host [S]    tensor index of each segment

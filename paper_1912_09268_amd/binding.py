@@ -190,7 +190,7 @@ def simulate(size_bytes: Sequence[int], t_backward_s: Sequence[float], t_forward
 
 TILE_HDR_DTYPE = np.dtype([("first_start", np.int64), ("first_end", np.int32), ("seg0", np.int32),
                            ("nseg", np.int32), ("valid", np.int32), ("layer0", np.int32),
-                           ("reserved", np.int32)])
+                           ("flags", np.int32)])
 
 
 class Context:

@@ -414,7 +414,7 @@ __device__ __forceinline__ TileHdr load_header(const TileHdr* p) {
     h.nseg = b[0];
     h.valid = b[1];
     h.layer0 = b[2];
-    h.reserved = b[3];
+    h.flags = b[3];
     return h;
 }
 
@@ -461,7 +461,7 @@ __global__ void __launch_bounds__(MGWFBP_BLOCK) mgwfbp_stream_kernel(const Args<
             // (ordinary loads and stores); all other w, v traffic is streamed past it like the gradients.
             // The two arms differ only in the cache policy of their memory instructions; the empty asm
             // statements keep the optimiser from merging them back into one (which drops the policy).
-            if (!updates(KIND) || (h.reserved & 1)) {
+            if (!updates(KIND) || (h.flags & 1)) {
                 asm volatile("; w and v cacheable" ::: "memory");
                 fast_tile<KIND, GradT, PT, NT_WV>(A, mrg, h.layer0, -h.first_start, tile_base);
                 asm volatile("; end w and v cacheable" ::: "memory");
@@ -523,10 +523,10 @@ void mark_resident_tiles(HostTables& h, uint64_t budget) {
     for (TileHdr& t : h.tiles) {
         const uint64_t need = static_cast<uint64_t>(t.valid) * 8u;
         if (used + need <= budget) {
-            t.reserved = 1;
+            t.flags = 1;
             used += need;
         } else {
-            t.reserved = 0;
+            t.flags = 0;
         }
     }
 }

@@ -76,7 +76,7 @@ int mgwfbp_build_tables(const uint64_t* n_elems, int32_t L, const uint8_t* merge
                 h.nseg = static_cast<int32_t>(e - s + 1);
                 h.valid = static_cast<int32_t>(valid);
                 h.layer0 = out.seg_layer[s];
-                h.reserved = 0;
+                h.flags = 0;
                 out.tiles.push_back(h);
             }
             next_tile += ntile;

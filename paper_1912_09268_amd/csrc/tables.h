@@ -32,7 +32,7 @@ struct TileHdr {          // 32 bytes, read with two 16-byte loads
     int32_t nseg;         // segments that intersect the tile, >= 1
     int32_t valid;        // leading elements of the tile that belong to the group, 1..TILE
     int32_t layer0;       // tensor index of segment seg0
-    int32_t reserved;
+    int32_t flags;        // bit 0: weights and momenta of this tile are kept cacheable (see kernels.hip)
 };
 static_assert(sizeof(TileHdr) == 32, "TileHdr must stay 32 bytes");
 
