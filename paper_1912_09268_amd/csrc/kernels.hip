@@ -1,8 +1,8 @@
 // Device side of the MG-WFBP library for gfx950 (MI355X): context management and the streaming
 // kernels pack / reduce / unpack_update and their fused forms.
 //
-// All five operations are the same walk over the merge arena, tile by tile (one workgroup of 256
-// lanes = 4 wavefronts per tile, workgroups stride over tiles):
+// All five operations are the same walk over the merge arena, tile by tile (by default one workgroup
+// of 256 lanes = 4 wavefronts per tile, dispatched in tile order):
 //
 //   kind            reads                          writes
 //   PACK            per-layer gradients (P)        merge arenas (P)                     Sec. 5.3
@@ -26,7 +26,13 @@
 // end of the group fall back to element-wise accesses.
 //
 // This is bandwidth-bound streaming work (at most 4 flops per 12+ bytes), so there is no use for
-// the matrix cores; the job is to keep enough 16-byte requests in flight on every compute unit.
+// the matrix cores; the job is to keep enough 16-byte requests in flight on every compute unit and to
+// present them to the memory system in a friendly order:
+//   - gradients, merge arenas and the reduced arena are touched once per iteration and are streamed
+//     (non-temporal loads / stores); a leading share of the weights and momenta, which come back next
+//     iteration, uses ordinary accesses so that it stays in the 256 MB memory-side cache (tile flag);
+//   - PACK, which has no arithmetic across workers, runs as P single-worker copies (gridDim.y = P),
+//     so the chip streams 2 arrays at a time instead of 2P.
 //
 // Arithmetic contract: binary32, one rounding per operation.  The file must be compiled with
 // -ffp-contract=off so that mu*v + g and w - lr*v are never fused.

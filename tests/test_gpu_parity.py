@@ -44,7 +44,7 @@ def _run_mode(dm, mode, lr, mu, G):
         raise KeyError(mode)
 
 
-def check_case(profile, merged, mode, misalign=0, steps=1, seed=W.BASE_SEED, label=""):
+def check_case(profile, merged, mode, misalign=0, steps=1, seed=W.BASE_SEED, label="", launch=None, resident=None):
     """Run `steps` iterations on the GPU and in the oracle from the same host arrays and compare every
     output: P merge arenas, the reduced arena, weights and momenta, and the padding of the arenas."""
     import torch
@@ -57,6 +57,10 @@ def check_case(profile, merged, mode, misalign=0, steps=1, seed=W.BASE_SEED, lab
     merged = [int(x) for x in merged]
     gdt = M.BF16 if profile.grad_dtype == "bf16" else M.F32
     ctx = M.Context(n, merged, profile.P, gdt)
+    if launch is not None:
+        ctx.set_launch(*launch)
+    if resident is not None:
+        ctx.set_resident_bytes(resident)
     dm = H.DeviceModel(ctx, n, misalign=misalign, fill_arena=True)
     off, grp, base, ge = ctx.layout()
     groups = OP.groups_in_arrival_order(merged)
@@ -238,6 +242,18 @@ def test_device_entry_points_reject_bad_arguments():
     ctx.close()
 
 
+@pytest.mark.parametrize("launch", [(1, False, 0), (2, True, 0), (0, True, 0), (0, False, 2), (0, False, 4),
+                                    (3, True, 3), (4096, False, 1024)])
+def test_results_do_not_depend_on_launch_shape(launch):
+    """Grid cap, die-contiguous numbering, tiles per workgroup and the cacheable share of w and v change how
+    the work is dealt out, never what is computed."""
+    rng = np.random.default_rng(77)
+    p = W.make_random_profile(rng, 60, size_lo=1, size_hi=40000, P=8, allow_empty=True)
+    merged = [0] + [int(x) for x in (rng.random(p.L - 1) < 0.5)]
+    for mode, resident in (("pipeline", 0), ("staged", 1 << 20), ("reduce_update", None), ("staged_per_group", 3 << 18)):
+        check_case(p, merged, mode, launch=launch, resident=resident, label=f"launch={launch}")
+
+
 # ------------------------------------------------------------------------------------------
 # the benchmark configurations at full size, in the launch configuration bench.py times
 # ------------------------------------------------------------------------------------------
@@ -249,6 +265,14 @@ def test_device_entry_points_reject_bad_arguments():
 def test_full_size_profiles(name, mode):
     p = W.make_profile(name)
     check_case(p, _plan_of(p), mode, steps=1)
+
+
+@pytest.mark.parametrize("name,tiles_per_wg", [("resnet50", 1), ("vgg16", 2)])
+def test_full_size_in_the_benchmarks_own_launch_configuration(name, tiles_per_wg):
+    """bench.py times the fused pipeline without the optional reduced arena and with the tiles-per-workgroup
+    value its tuning step picks (1 on the ResNet-50 shape, 2 on the VGG-16 shape)."""
+    p = W.make_profile(name)
+    check_case(p, _plan_of(p), "pipeline_no_reduced", steps=1, launch=(0, False, tiles_per_wg))
 
 
 # ------------------------------------------------------------------------------------------
