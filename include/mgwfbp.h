@@ -265,6 +265,13 @@ int mgwfbp_group_pipeline(mgwfbp_ctx* ctx, int32_t group, const void* const* d_g
                           float* const* d_w_ptrs, float* const* d_v_ptrs,
                           float lr, float momentum, void* hip_stream);
 
+/* mgwfbp_group_pipeline for the consecutive groups group_first .. group_first + group_count - 1 in one
+ * launch (e.g. all groups whose buffers filled since the last call).  group_count = 0 is a no-op. */
+int mgwfbp_group_pipeline_span(mgwfbp_ctx* ctx, int32_t group_first, int32_t group_count,
+                               const void* const* d_grad_ptrs, void* const* d_merge_bufs, float* d_reduced,
+                               float* const* d_w_ptrs, float* const* d_v_ptrs,
+                               float lr, float momentum, void* hip_stream);
+
 /* ---------------------------------------------------------------------------------------------
  * Diagnostics
  * ------------------------------------------------------------------------------------------- */

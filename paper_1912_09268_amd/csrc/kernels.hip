@@ -818,6 +818,19 @@ int mgwfbp_group_pipeline(mgwfbp_ctx* c, int32_t group, const void* const* d_gra
                            hip_stream);
 }
 
+int mgwfbp_group_pipeline_span(mgwfbp_ctx* c, int32_t group_first, int32_t group_count,
+                               const void* const* d_grad_ptrs, void* const* d_merge_bufs, float* d_reduced,
+                               float* const* d_w_ptrs, float* const* d_v_ptrs, float lr, float momentum,
+                               void* hip_stream) {
+    if (c == nullptr || !c->on_device) return MGWFBP_EINVAL;
+    if (group_first < 0 || group_count < 0 || group_first > c->host.G - group_count) return MGWFBP_EINVAL;
+    Span s;                                   // consecutive groups own consecutive tiles
+    s.t0 = c->host.group_tile[static_cast<size_t>(group_first)];
+    s.t1 = c->host.group_tile[static_cast<size_t>(group_first + group_count)];
+    return run<K_PIPELINE>(c, 0, d_grad_ptrs, d_merge_bufs, d_reduced, d_w_ptrs, d_v_ptrs, lr, momentum,
+                           hip_stream, &s);
+}
+
 int mgwfbp_last_hip_error(void) { return g_last_hip_error; }
 
 const char* mgwfbp_version(void) { return "mgwfbp-gfx950 0.1"; }

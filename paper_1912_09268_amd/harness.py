@@ -140,3 +140,9 @@ class DeviceModel:
         self.ctx.group_pipeline(group, self.grad_ptrs.data_ptr(), self.merge_ptrs.data_ptr(),
                                 self.reduced.data_ptr() if write_reduced else 0,
                                 self.w_ptrs.data_ptr(), self.v_ptrs.data_ptr(), lr, momentum, self._stream())
+
+    def group_pipeline_span(self, lr: float, momentum: float, group_first: int, group_count: int,
+                            write_reduced: bool = True) -> None:
+        self.ctx.group_pipeline_span(group_first, group_count, self.grad_ptrs.data_ptr(), self.merge_ptrs.data_ptr(),
+                                     self.reduced.data_ptr() if write_reduced else 0,
+                                     self.w_ptrs.data_ptr(), self.v_ptrs.data_ptr(), lr, momentum, self._stream())

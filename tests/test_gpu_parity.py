@@ -12,7 +12,8 @@ from oracle import plan as OP
 
 pytestmark = pytest.mark.gpu
 
-MODES = ("staged", "staged_per_group", "reduce_update", "pipeline", "pipeline_per_group", "pipeline_no_reduced")
+MODES = ("staged", "staged_per_group", "reduce_update", "pipeline", "pipeline_per_group", "pipeline_no_reduced",
+         "pipeline_spans")
 
 
 def _say(msg):
@@ -40,6 +41,15 @@ def _run_mode(dm, mode, lr, mu, G):
             dm.group_pipeline(lr, mu, k)
     elif mode == "pipeline_no_reduced":
         dm.group_pipeline(lr, mu, write_reduced=False)
+    elif mode == "pipeline_spans":                # a few consecutive groups per launch, plus an empty span
+        k = 0
+        width = 1
+        while k < G:
+            n = min(width, G - k)
+            dm.group_pipeline_span(lr, mu, k, n)
+            k += n
+            width = width % 3 + 1
+        dm.group_pipeline_span(lr, mu, G, 0)
     else:
         raise KeyError(mode)
 
@@ -143,7 +153,7 @@ def test_random_models_worker_counts(P, dtype):
     rng = np.random.default_rng(1000 + P)
     p = W.make_random_profile(rng, 50, size_hi=20000, P=P, grad_dtype=dtype, allow_empty=True)
     merged = [0] + [int(x) for x in (rng.random(p.L - 1) < 0.6)]
-    for mode in ("staged", "pipeline", "reduce_update"):
+    for mode in ("staged", "pipeline", "reduce_update", "pipeline_spans"):
         check_case(p, merged, mode, label=f"random P={P}")
 
 
@@ -239,6 +249,10 @@ def test_device_entry_points_reject_bad_arguments():
         ctx.pack(0, 0, dm.merge_ptrs.data_ptr())     # null pointer table
     with pytest.raises(M.MgwfbpError):
         ctx.reduce(0, dm.merge_ptrs.data_ptr(), 0)   # null reduced arena
+    with pytest.raises(M.MgwfbpError):
+        dm.group_pipeline_span(0.1, 0.9, 1, 1)       # the model has one group only
+    with pytest.raises(M.MgwfbpError):
+        dm.group_pipeline_span(0.1, 0.9, -1, 1)
     ctx.close()
 
 
