@@ -157,6 +157,18 @@ def test_random_models_worker_counts(P, dtype):
         check_case(p, merged, mode, label=f"random P={P}")
 
 
+@pytest.mark.parametrize("P", [33, 64])
+def test_largest_worker_counts(P):
+    import paper_1912_09268_amd as M
+    rng = np.random.default_rng(2000 + P)
+    p = W.make_random_profile(rng, 12, size_hi=9000, P=P, grad_dtype="bf16" if P == 33 else "f32")
+    merged = [0] + [int(x) for x in (rng.random(p.L - 1) < 0.5)]
+    for mode in ("staged", "pipeline"):
+        check_case(p, merged, mode, label=f"P={P}")
+    with pytest.raises(M.MgwfbpError):
+        M.Context([4, 4], [0, 1], 65, M.F32)
+
+
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 @pytest.mark.parametrize("mode", ["staged", "pipeline"])
 def test_misaligned_sources_and_odd_sizes(dtype, mode):
