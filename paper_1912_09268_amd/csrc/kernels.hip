@@ -230,18 +230,28 @@ __device__ __forceinline__ void store_phase(Regs<GradT, PT, W>& R, const Args<Gr
             }
         }
     } else {
-        // any P: stream the workers one after the other (same order, same roundings)
+        // any P: take the workers four at a time (four loads in flight), accumulating in worker order
         FV acc;
-        for (int w = 0; w < A.P; ++w) {
-            GV g;
-            if constexpr (reads_grads(KIND)) g = ld<NT_LD, GV>(src.get(w) + soff);
-            else if constexpr (reads_merge(KIND)) g = ld<NT_LD, GV>(mrg.get(w) + apos);
-            if constexpr (writes_merge(KIND)) st<NT_ST, GV>(mrg.get(w) + apos, g);
-            if constexpr (sums(KIND)) {
+        for (int w0 = 0; w0 < A.P; w0 += 4) {
+            GV g[4];
 #pragma unroll
-                for (int c = 0; c < N; ++c) {
-                    const float x = widen(comp(g, c));
-                    setc(acc, c, w == 0 ? x : comp(acc, c) + x);
+            for (int j = 0; j < 4; ++j) {
+                if (w0 + j < A.P) {
+                    if constexpr (reads_grads(KIND)) g[j] = ld<NT_LD, GV>(src.get(w0 + j) + soff);
+                    else if constexpr (reads_merge(KIND)) g[j] = ld<NT_LD, GV>(mrg.get(w0 + j) + apos);
+                }
+            }
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                if (w0 + j < A.P) {
+                    if constexpr (writes_merge(KIND)) st<NT_ST, GV>(mrg.get(w0 + j) + apos, g[j]);
+                    if constexpr (sums(KIND)) {
+#pragma unroll
+                        for (int c = 0; c < N; ++c) {
+                            const float x = widen(comp(g[j], c));
+                            setc(acc, c, (w0 + j) == 0 ? x : comp(acc, c) + x);
+                        }
+                    }
                 }
             }
         }
