@@ -59,6 +59,12 @@ def test_plan_hand_example_and_equality_case():
     assert merged.tolist() == [0, 0]
 
 
+def test_plan_four_layer_hand_example():
+    merged, first = M.plan([1, 1, 1, 100], [3.0, 5.0, 0.5, 0.0], 1.0, 1.0)
+    assert merged.tolist() == [0, 1, 0, 1] and first.tolist() == [3, 1]
+    assert M.eval_plan(merged, [1, 1, 1, 100], [3.0, 5.0, 0.5, 0.0], 1.0, 1.0) == pytest.approx(105.5)
+
+
 def test_plan_degenerate_and_invalid_inputs():
     merged, first = M.plan([], [], 1.0, 1.0)
     assert merged.size == 0 and first.size == 0

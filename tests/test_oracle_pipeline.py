@@ -109,9 +109,11 @@ def test_reduce_replayed_in_binary64_with_explicit_rounding():
 
 
 def test_reduce_non_power_of_two_uses_reciprocal_multiply():
-    bufs = [np.array([1.0], np.float32)] * 3
+    # sum 5 over three workers: 5 * float32(1/3) and 5 / 3 round to different binary32 values
+    bufs = [np.array([1.0], np.float32), np.array([1.0], np.float32), np.array([3.0], np.float32)]
     third = np.float32(1.0) / np.float32(3.0)
-    assert OD.reduce_average(bufs)[0] == np.float32(3.0) * third
+    assert np.float32(5.0) * third != np.float32(5.0) / np.float32(3.0)
+    assert OD.reduce_average(bufs)[0] == np.float32(5.0) * third
 
 
 def test_reduce_bf16_inputs_accumulate_in_binary32():

@@ -176,6 +176,16 @@ def test_algorithm1_on_hand_example_and_theorem_gap():
     assert t_best < t_greedy < OP.wfbp_time(HAND_BYTES, HAND_TB, 1.0, 1.0)
 
 
+def test_algorithm1_followed_by_hand_on_four_layers():
+    """The message time of a layer that received merged bytes must be re-derived: two levels further down
+    the decision depends on it."""
+    *flags, t = _rows("hand_plan_L4.txt")[0]
+    by, tb = [1, 1, 1, 100], [3.0, 5.0, 0.5, 0.0]
+    m = OP.plan_algorithm1(by, tb, 1.0, 1.0)
+    assert m == [int(f) for f in flags]
+    assert OP.iteration_time(m, by, tb, 1.0, 1.0) == pytest.approx(float(t))
+
+
 def test_each_decision_matches_the_layer_type_rule():
     """Layer l is merged iff tau_b^(l-1) + t_b^(l-1) < tau_c^(l) + a, with tau_c^(l) taken from the
     timeline in which the decisions for layers above l are already applied and layers <= l normal."""
