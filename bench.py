@@ -132,7 +132,14 @@ def cpu_baseline(profile, merged, bytes_per_step, budget_s=10.0):
         OD.merged_step(grads, groups, w, v, profile.lr, profile.momentum)
         times.append(time.perf_counter() - t0)
     best = min(times)
-    return {"value": bytes_per_step / best / 1e9, "unit": "GB/s", "cores": 1, "kind": "oracle",
+    by = [int(x) for x in profile.size_bytes]
+    tb = [float(x) for x in profile.t_backward]
+    plan_times = []
+    for _ in range(5):
+        t0 = time.perf_counter()
+        OP.plan_algorithm1(by, tb, profile.a, profile.b)
+        plan_times.append((time.perf_counter() - t0) * 1e6)
+    return {"plan_us": round(statistics.median(plan_times), 1), "value": bytes_per_step / best / 1e9, "unit": "GB/s", "cores": 1, "kind": "oracle",
             "sample": f"{len(times)} full step(s) of the {profile.name} workload (all groups, P={profile.P}); "
                       f"best {best * 1e3:.0f} ms/step; same byte count as `value`",
             "ms_per_step": best * 1e3, "host_cpus": os.cpu_count()}
