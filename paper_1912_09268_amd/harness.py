@@ -38,6 +38,7 @@ class DeviceModel:
         self.device = torch.device(device)
         self.gdt = _torch_dtype(ctx.grad_dtype)
         self.misalign = int(misalign)
+        self._slabs = []
         self.grads: List[List[torch.Tensor]] = [self._alloc_layers(self.gdt) for _ in range(self.P)]
         self.w = self._alloc_layers(torch.float32)
         self.v = self._alloc_layers(torch.float32)
@@ -59,8 +60,23 @@ class DeviceModel:
         for i, n in enumerate(self.n_elems):
             shift = 1 + (i * self.misalign) % 7
             slab = torch.empty(n + 16, dtype=dtype, device=self.device)
+            if dtype == torch.float32:
+                slab.view(torch.int32).fill_(SENTINEL32)
+            else:
+                slab.fill_(SENTINEL16)
+            self._slabs.append((slab, shift, n))
             out.append(slab[shift:shift + n])
         return out
+
+    def guard_bands_intact(self) -> bool:
+        """In misaligned mode every per-layer tensor sits inside a slab with spare elements on both sides,
+        pre-filled with a sentinel pattern: True if no call has written there."""
+        for slab, shift, n in self._slabs:
+            raw = slab.view(torch.int32) if slab.dtype == torch.float32 else slab
+            want = SENTINEL32 if slab.dtype == torch.float32 else SENTINEL16
+            if not bool((raw[:shift] == want).all()) or not bool((raw[shift + n:] == want).all()):
+                return False
+        return True
 
     def _ptr_table(self, tensors: Sequence[torch.Tensor]) -> torch.Tensor:
         addrs = np.asarray([t.data_ptr() for t in tensors] or [0], dtype=np.int64)

@@ -124,6 +124,7 @@ def check_case(profile, merged, mode, misalign=0, steps=1, seed=W.BASE_SEED, lab
         v_ref = np.concatenate(v_o) if v_o else np.zeros(0, np.float32)
         assert np.array_equal(_bits(v_dev), _bits(v_ref)), "momentum"
         assert np.array_equal(_bits(w_dev), _bits(w_ref)), "weights"
+        assert dm.guard_bands_intact(), "a per-layer tensor was written outside its bounds"
         dm.fill_arenas()
     ctx.close()
 
