@@ -38,6 +38,8 @@
  *       r = ((..((g_0 + g_1) + g_2)..) + g_{P-1}) * (1.0f / P)
  *       t1 = mu * v ; v' = t1 + r ; t2 = eta * v' ; w' = w - t2
  *     bfloat16 gradients are widened exactly to binary32 before the first addition.
+ *   - A context is used by one host thread at a time (its launch settings are plain fields); different
+ *     contexts are independent, and the host-only functions are re-entrant.
  *   - Every function returns MGWFBP_OK (0) or a negative mgwfbp_status.  Nothing throws or aborts.
  *     A failed call has enqueued nothing.
  */
