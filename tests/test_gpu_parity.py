@@ -503,3 +503,44 @@ def test_tensor_with_more_than_two_to_the_31_elements():
     tail = window(dm.merge[0], end, ctx.arena_elems)
     assert (tail == H.SENTINEL16).all()
     ctx.close()
+
+
+# ------------------------------------------------------------------------------------------
+# the cost model fitted to a measured size sweep of the reduce step (Sec. 6.2's method, one GPU)
+# ------------------------------------------------------------------------------------------
+
+def test_fit_ab_on_a_measured_reduce_sweep():
+    """Time mgwfbp_reduce over single-group models of growing size and fit T = a + b*M as the paper does for
+    its all-reduce (Fig. 4).  Only sanity bounds are asserted: a is a launch cost of microseconds, 1/b a
+    memory rate of terabytes per second, and the line explains the measurements."""
+    import torch
+    import paper_1912_09268_amd as M
+    from paper_1912_09268_amd import harness as H
+    P = 8
+    sizes, times = [], []
+    for n in (1 << 16, 1 << 18, 1 << 20, 1 << 22, 1 << 24, 1 << 25, 1 << 26):
+        ctx = M.Context([n], [0], P, M.F32)
+        dm = H.DeviceModel(ctx, [n])
+        for m in dm.merge:
+            m.normal_()
+        for _ in range(5):
+            dm.reduce(0)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        reps = 30
+        e0.record()
+        for _ in range(reps):
+            dm.reduce(0)
+        e1.record()
+        torch.cuda.synchronize()
+        sizes.append(n * 4)                                   # message bytes of one worker's slice
+        times.append(e0.elapsed_time(e1) * 1e-3 / reps)
+        ctx.close()
+    a, b = M.fit_ab(sizes, times)
+    rate = (P * 4 + 4) / 4 / b / 1e12                         # bytes moved per message byte, over b
+    _say(f"[fit] reduce sweep: a = {a * 1e6:.2f} us, b = {b * 1e12:.3f} ps/B -> {rate:.2f} TB/s of traffic; "
+         f"times {[round(t * 1e6, 1) for t in times]} us")
+    assert -50e-6 < a < 100e-6      # small launches sit on a flat ~8 us floor, so the intercept is loosely determined
+    assert 2.0 < rate < 8.0
+    worst = max(abs(a + b * s - t) / t for s, t in zip(sizes[3:], times[3:]))
+    assert worst < 0.25
