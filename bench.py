@@ -203,13 +203,32 @@ def main() -> int:
     n = [int(x) for x in p.n_elems]
     g = p.elem_bytes
 
-    # plan: one-time host computation, timed on its own
+    # plan: one-time host computation, timed on its own -- once through the Python binding (argument
+    # marshalling included) and once as the bare C-ABI call with the arguments marshalled beforehand
+    import ctypes as C
     plan_times = []
     for _ in range(1000 if p.L <= 1000 else 100):
         t0 = time.perf_counter()
         merged, first = M.plan(p.size_bytes, p.t_backward, p.a, p.b)
         plan_times.append((time.perf_counter() - t0) * 1e6)
+    plan_us_binding = statistics.median(plan_times)
+    sz = np.ascontiguousarray(p.size_bytes, np.uint64)
+    tb = np.ascontiguousarray(p.t_backward, np.float64)
+    m_out = np.zeros(p.L, np.uint8)
+    f_out = np.zeros(p.L + 1, np.int32)
+    g_out = C.c_int32(0)
+    raw = M.lib().mgwfbp_plan
+    c_args = (sz.ctypes.data_as(C.POINTER(C.c_uint64)), tb.ctypes.data_as(C.POINTER(C.c_double)), p.L,
+              C.c_double(p.a), C.c_double(p.b), m_out.ctypes.data_as(C.POINTER(C.c_uint8)),
+              f_out.ctypes.data_as(C.POINTER(C.c_int32)), C.byref(g_out))
+    plan_times = []
+    for _ in range(200):
+        t0 = time.perf_counter()
+        for _ in range(20):
+            raw(*c_args)
+        plan_times.append((time.perf_counter() - t0) * 1e6 / 20)
     plan_us = statistics.median(plan_times)
+    assert m_out.tolist() == merged.tolist()
     G = int(first.shape[0])
 
     ctx = M.Context(n, merged, p.P, M.BF16 if p.grad_dtype == "bf16" else M.F32)
@@ -247,7 +266,7 @@ def main() -> int:
                    "xcd_contiguous": bool(args.xcd_contiguous),
                    "tiles_per_workgroup": tpw or "default", "autotune_ms": tuned},
         "pct_of_hbm_peak": round(100.0 * value / HBM_PEAK_GBPS, 2),
-        "plan_us": round(plan_us, 2),
+        "plan_us": round(plan_us, 2), "plan_us_through_python_binding": round(plan_us_binding, 2),
         "roofline": {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": round(achieved / HBM_PEAK_GBPS, 4),
                      "traffic": MEASURED_TRAFFIC_BYTES.get((args.workload, args.mode)),
