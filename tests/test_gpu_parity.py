@@ -544,3 +544,25 @@ def test_fit_ab_on_a_measured_reduce_sweep():
     assert 2.0 < rate < 8.0
     worst = max(abs(a + b * s - t) / t for s, t in zip(sizes[3:], times[3:]))
     assert worst < 0.25
+
+
+# ------------------------------------------------------------------------------------------
+# broad randomised coverage: many small models with random shapes, plans, worker counts and alignments
+# ------------------------------------------------------------------------------------------
+
+@pytest.mark.parametrize("block", range(6))
+def test_many_random_models(block):
+    rng = np.random.default_rng(9000 + block)
+    for case in range(10):
+        L = int(rng.integers(1, 90))
+        hi = int(rng.choice([8, 300, 3000, 30000]))
+        P = int(rng.choice([1, 2, 3, 4, 5, 8, 16]))
+        dtype = str(rng.choice(["f32", "bf16"]))
+        p = W.make_random_profile(rng, L, size_lo=1, size_hi=hi, P=P, grad_dtype=dtype, allow_empty=bool(rng.integers(0, 2)))
+        merged = [0] + [int(x) for x in (rng.random(L - 1) < rng.choice([0.1, 0.5, 0.9]))]
+        mode = str(rng.choice(["staged", "staged_per_group", "reduce_update", "pipeline", "pipeline_per_group",
+                               "pipeline_spans"]))
+        launch = (int(rng.choice([0, 1, 3])), bool(rng.integers(0, 2)), int(rng.choice([0, 1, 2, 5])))
+        check_case(p, merged, mode, misalign=int(rng.choice([0, 0, 3, 5])), launch=launch,
+                   resident=int(rng.choice([0, 1 << 16, 1 << 30])), seed=int(rng.integers(1, 10 ** 6)),
+                   label=f"random block {block} case {case}")
