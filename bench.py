@@ -39,6 +39,8 @@ def bytes_per_element(mode: str, P: int, g: int) -> int:
     mode = mode[:-len("_graph")] if mode.endswith("_graph") else mode
     if mode in ("pipeline", "pipeline_per_group"):
         return 2 * P * g + 16            # read P grads, write P merge, read+write w and v
+    if mode == "direct":
+        return P * g + 16                # read P grads, read+write w and v; no merge arenas
     if mode == "reduce_update":
         return 2 * P * g + (P * g + 16)  # pack, then merge -> w, v
     if mode in ("staged", "staged_per_group"):
@@ -48,7 +50,7 @@ def bytes_per_element(mode: str, P: int, g: int) -> int:
 
 def launches_per_step(mode: str, G: int) -> int:
     mode = mode[:-len("_graph")] if mode.endswith("_graph") else mode
-    return {"pipeline": 1, "pipeline_per_group": G, "reduce_update": 2, "staged": 3, "staged_per_group": 3 * G}[mode]
+    return {"pipeline": 1, "pipeline_per_group": G, "direct": 1, "reduce_update": 2, "staged": 3, "staged_per_group": 3 * G}[mode]
 
 
 def run_step(dm, mode: str, lr: float, mu: float, G: int) -> None:
@@ -57,6 +59,8 @@ def run_step(dm, mode: str, lr: float, mu: float, G: int) -> None:
     elif mode == "pipeline_per_group":
         for k in range(G):
             dm.group_pipeline(lr, mu, k, write_reduced=False)
+    elif mode == "direct":
+        dm.direct_update(lr, mu, -1)
     elif mode == "reduce_update":
         dm.pack(-1); dm.reduce_update(lr, mu, -1)
     elif mode == "staged":
@@ -152,7 +156,7 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="resnet50")
     ap.add_argument("--mode", default="pipeline",
-                    choices=["pipeline", "pipeline_per_group", "reduce_update", "staged", "staged_per_group",
+                    choices=["pipeline", "pipeline_per_group", "direct", "reduce_update", "staged", "staged_per_group",
                              "pipeline_per_group_graph", "staged_per_group_graph"])
     ap.add_argument("--all-modes", action="store_true", help="also time the other launch modes (extra keys)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -278,7 +282,7 @@ def main() -> int:
                             "(Sec. 5.3) and calls the plan a one-time O(L^2) computation (Sec. 4.2)")
     if args.all_modes:
         others = {}
-        for mode in ("pipeline", "pipeline_per_group", "pipeline_per_group_graph", "reduce_update", "staged",
+        for mode in ("pipeline", "pipeline_per_group", "pipeline_per_group_graph", "direct", "reduce_update", "staged",
                      "staged_per_group", "staged_per_group_graph"):
             if mode == args.mode:
                 continue

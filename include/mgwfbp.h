@@ -267,6 +267,16 @@ int mgwfbp_group_pipeline(mgwfbp_ctx* ctx, int32_t group, const void* const* d_g
                           float* const* d_w_ptrs, float* const* d_v_ptrs,
                           float lr, float momentum, void* hip_stream);
 
+/* reduce + update straight from the per-layer gradients, for the case in which all P workers'
+ * gradients are on this device and nothing has to be transmitted: the merge buffers of Sec. 5.3 are
+ * never written (they exist to give the all-reduce one contiguous message).  Walks the same group /
+ * offset table, so `group` means what it means everywhere else; optionally writes the averaged
+ * gradient to d_reduced (NULL to skip).  Same bits in w, v and d_reduced as mgwfbp_group_pipeline
+ * (Eq. 2 with the sum taken in worker order). */
+int mgwfbp_direct_update(mgwfbp_ctx* ctx, int32_t group, const void* const* d_grad_ptrs, float* d_reduced,
+                         float* const* d_w_ptrs, float* const* d_v_ptrs,
+                         float lr, float momentum, void* hip_stream);
+
 /* mgwfbp_group_pipeline for the consecutive groups group_first .. group_first + group_count - 1 in one
  * launch (e.g. all groups whose buffers filled since the last call).  group_count = 0 is a no-op. */
 int mgwfbp_group_pipeline_span(mgwfbp_ctx* ctx, int32_t group_first, int32_t group_count,

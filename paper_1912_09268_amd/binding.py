@@ -60,6 +60,7 @@ _SIGNATURES = {
     "mgwfbp_unpack_update": (C.c_int, [_vp, C.c_int32, _vp, _vp, _vp, C.c_float, C.c_float, _vp]),
     "mgwfbp_reduce_update": (C.c_int, [_vp, C.c_int32, _vp, _vp, _vp, C.c_float, C.c_float, _vp]),
     "mgwfbp_group_pipeline": (C.c_int, [_vp, C.c_int32, _vp, _vp, _vp, _vp, _vp, C.c_float, C.c_float, _vp]),
+    "mgwfbp_direct_update": (C.c_int, [_vp, C.c_int32, _vp, _vp, _vp, _vp, C.c_float, C.c_float, _vp]),
     "mgwfbp_group_pipeline_span": (C.c_int, [_vp, C.c_int32, C.c_int32, _vp, _vp, _vp, _vp, _vp, C.c_float, C.c_float, _vp]),
     "mgwfbp_last_hip_error": (C.c_int, []),
     "mgwfbp_version": (C.c_char_p, []),
@@ -286,6 +287,12 @@ class Context:
         _check("mgwfbp_group_pipeline", lib().mgwfbp_group_pipeline(
             self._h, int(group), _vp(d_grad_ptrs), _vp(d_merge_bufs), _vp(d_reduced or None), _vp(d_w_ptrs),
             _vp(d_v_ptrs), float(lr), float(momentum), _vp(stream)))
+
+    def direct_update(self, group: int, d_grad_ptrs: int, d_reduced: int, d_w_ptrs: int, d_v_ptrs: int,
+                      lr: float, momentum: float, stream: int = 0) -> None:
+        _check("mgwfbp_direct_update", lib().mgwfbp_direct_update(
+            self._h, int(group), _vp(d_grad_ptrs), _vp(d_reduced or None), _vp(d_w_ptrs), _vp(d_v_ptrs),
+            float(lr), float(momentum), _vp(stream)))
 
     def group_pipeline_span(self, group_first: int, group_count: int, d_grad_ptrs: int, d_merge_bufs: int,
                             d_reduced: int, d_w_ptrs: int, d_v_ptrs: int, lr: float, momentum: float,

@@ -1,7 +1,7 @@
 // Device side of the MG-WFBP library for gfx950 (MI355X): context management and the streaming
 // kernels pack / reduce / unpack_update and their fused forms.
 //
-// All five operations are the same walk over the merge arena, tile by tile (by default one workgroup
+// All six operations are the same walk over the merge arena, tile by tile (by default one workgroup
 // of 256 lanes = 4 wavefronts per tile, dispatched in tile order):
 //
 //   kind            reads                          writes
@@ -10,6 +10,7 @@
 //   UPDATE          reduced arena, w, v            w, v                                 Eq. 2 (update)
 //   REDUCE_UPDATE   merge arenas (P), w, v         w, v
 //   PIPELINE        per-layer gradients (P), w, v  merge arenas (P), [reduced], w, v
+//   DIRECT          per-layer gradients (P), w, v  [reduced], w, v
 //
 // The arena side of every access is 16-byte aligned (tiles start on multiples of the tile size and
 // lanes step in 4-element vectors).  The per-layer side starts wherever the tensor starts, so it is
@@ -60,14 +61,14 @@ constexpr int TVECS = MGWFBP_TILE_VECS;
 constexpr int TILE = MGWFBP_TILE_ELEMS;
 constexpr int MAXSEG = MGWFBP_MAXSEG;
 
-enum Kind { K_PACK = 0, K_REDUCE = 1, K_UPDATE = 2, K_REDUCE_UPDATE = 3, K_PIPELINE = 4 };
+enum Kind { K_PACK = 0, K_REDUCE = 1, K_UPDATE = 2, K_REDUCE_UPDATE = 3, K_PIPELINE = 4, K_DIRECT = 5 };
 
-constexpr bool reads_grads(int k) { return k == K_PACK || k == K_PIPELINE; }
+constexpr bool reads_grads(int k) { return k == K_PACK || k == K_PIPELINE || k == K_DIRECT; }
 constexpr bool reads_merge(int k) { return k == K_REDUCE || k == K_REDUCE_UPDATE; }
 constexpr bool writes_merge(int k) { return k == K_PACK || k == K_PIPELINE; }
-constexpr bool sums(int k) { return k == K_REDUCE || k == K_REDUCE_UPDATE || k == K_PIPELINE; }
-constexpr bool writes_reduced(int k) { return k == K_REDUCE || k == K_PIPELINE; }
-constexpr bool updates(int k) { return k == K_UPDATE || k == K_REDUCE_UPDATE || k == K_PIPELINE; }
+constexpr bool sums(int k) { return k == K_REDUCE || k == K_REDUCE_UPDATE || k == K_PIPELINE || k == K_DIRECT; }
+constexpr bool writes_reduced(int k) { return k == K_REDUCE || k == K_PIPELINE || k == K_DIRECT; }
+constexpr bool updates(int k) { return k == K_UPDATE || k == K_REDUCE_UPDATE || k == K_PIPELINE || k == K_DIRECT; }
 constexpr bool needs_owner(int k) { return k != K_REDUCE; }
 
 // ---------------------------------------------------------------------------------------------
@@ -839,6 +840,12 @@ int mgwfbp_group_pipeline_span(mgwfbp_ctx* c, int32_t group_first, int32_t group
     s.t1 = c->host.group_tile[static_cast<size_t>(group_first + group_count)];
     return run<K_PIPELINE>(c, 0, d_grad_ptrs, d_merge_bufs, d_reduced, d_w_ptrs, d_v_ptrs, lr, momentum,
                            hip_stream, &s);
+}
+
+int mgwfbp_direct_update(mgwfbp_ctx* c, int32_t group, const void* const* d_grad_ptrs, float* d_reduced,
+                         float* const* d_w_ptrs, float* const* d_v_ptrs, float lr, float momentum,
+                         void* hip_stream) {
+    return run<K_DIRECT>(c, group, d_grad_ptrs, nullptr, d_reduced, d_w_ptrs, d_v_ptrs, lr, momentum, hip_stream);
 }
 
 int mgwfbp_last_hip_error(void) { return g_last_hip_error; }

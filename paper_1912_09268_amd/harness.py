@@ -157,6 +157,10 @@ class DeviceModel:
                                 self.reduced.data_ptr() if write_reduced else 0,
                                 self.w_ptrs.data_ptr(), self.v_ptrs.data_ptr(), lr, momentum, self._stream())
 
+    def direct_update(self, lr: float, momentum: float, group: int = -1, write_reduced: bool = False) -> None:
+        self.ctx.direct_update(group, self.grad_ptrs.data_ptr(), self.reduced.data_ptr() if write_reduced else 0,
+                               self.w_ptrs.data_ptr(), self.v_ptrs.data_ptr(), lr, momentum, self._stream())
+
     def group_pipeline_span(self, lr: float, momentum: float, group_first: int, group_count: int,
                             write_reduced: bool = True) -> None:
         self.ctx.group_pipeline_span(group_first, group_count, self.grad_ptrs.data_ptr(), self.merge_ptrs.data_ptr(),

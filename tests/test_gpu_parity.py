@@ -13,7 +13,9 @@ from oracle import plan as OP
 pytestmark = pytest.mark.gpu
 
 MODES = ("staged", "staged_per_group", "reduce_update", "pipeline", "pipeline_per_group", "pipeline_no_reduced",
-         "pipeline_spans")
+         "pipeline_spans", "direct", "direct_per_group_with_reduced")
+NO_REDUCED = ("reduce_update", "pipeline_no_reduced", "direct")
+NO_MERGE = ("direct", "direct_per_group_with_reduced")
 
 
 def _say(msg):
@@ -50,6 +52,11 @@ def _run_mode(dm, mode, lr, mu, G):
             k += n
             width = width % 3 + 1
         dm.group_pipeline_span(lr, mu, G, 0)
+    elif mode == "direct":                        # merge arenas never written
+        dm.direct_update(lr, mu)
+    elif mode == "direct_per_group_with_reduced":
+        for k in range(G):
+            dm.direct_update(lr, mu, k, write_reduced=True)
     else:
         raise KeyError(mode)
 
@@ -101,11 +108,12 @@ def check_case(profile, merged, mode, misalign=0, steps=1, seed=W.BASE_SEED, lab
             lo, hi = int(base[k]), int(base[k]) + int(ge[k])
             covered[lo:hi] = True
             bufs = [OD.pack(grads[w], [members])[0] for w in range(profile.P)]
-            for w in range(profile.P):
-                assert np.array_equal(_bits(merge_dev[w][lo:hi]), _bits(bufs[w])), f"merge arena w={w} group={k}"
+            if mode not in NO_MERGE:
+                for w in range(profile.P):
+                    assert np.array_equal(_bits(merge_dev[w][lo:hi]), _bits(bufs[w])), f"merge arena w={w} group={k}"
             r = OD.reduce_average(bufs)
             red_o.append(r)
-            if mode not in ("reduce_update", "pipeline_no_reduced"):
+            if mode not in NO_REDUCED:
                 assert np.array_equal(_bits(red_dev[lo:hi]), _bits(r)), f"reduced group={k}"
         # padding between groups is never written
         pad = ~covered
@@ -113,9 +121,11 @@ def check_case(profile, merged, mode, misalign=0, steps=1, seed=W.BASE_SEED, lab
             m = _bits(merge_dev[w])
             sent = H.SENTINEL32 if m.dtype == np.uint32 else H.SENTINEL16
             assert (m[pad] == sent).all(), "merge arena padding was written"
+            if mode in NO_MERGE:
+                assert (m == sent).all(), "merge arenas must stay untouched in this mode"
         r32 = _bits(red_dev)
         assert (r32[pad] == H.SENTINEL32).all(), "reduced arena padding was written"
-        if mode in ("reduce_update", "pipeline_no_reduced"):
+        if mode in NO_REDUCED:
             assert (r32 == H.SENTINEL32).all(), "reduced arena must stay untouched in this mode"
         OD.unpack_update(red_o, groups, w_o, v_o, profile.lr, profile.momentum)
         w_dev = dm.download_weights()
@@ -154,7 +164,7 @@ def test_random_models_worker_counts(P, dtype):
     rng = np.random.default_rng(1000 + P)
     p = W.make_random_profile(rng, 50, size_hi=20000, P=P, grad_dtype=dtype, allow_empty=True)
     merged = [0] + [int(x) for x in (rng.random(p.L - 1) < 0.6)]
-    for mode in ("staged", "pipeline", "reduce_update", "pipeline_spans"):
+    for mode in ("staged", "pipeline", "reduce_update", "pipeline_spans", "direct_per_group_with_reduced"):
         check_case(p, merged, mode, label=f"random P={P}")
 
 
@@ -164,14 +174,14 @@ def test_largest_worker_counts(P):
     rng = np.random.default_rng(2000 + P)
     p = W.make_random_profile(rng, 12, size_hi=9000, P=P, grad_dtype="bf16" if P == 33 else "f32")
     merged = [0] + [int(x) for x in (rng.random(p.L - 1) < 0.5)]
-    for mode in ("staged", "pipeline"):
+    for mode in ("staged", "pipeline", "direct"):
         check_case(p, merged, mode, label=f"P={P}")
     with pytest.raises(M.MgwfbpError):
         M.Context([4, 4], [0, 1], 65, M.F32)
 
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
-@pytest.mark.parametrize("mode", ["staged", "pipeline"])
+@pytest.mark.parametrize("mode", ["staged", "pipeline", "direct_per_group_with_reduced"])
 def test_misaligned_sources_and_odd_sizes(dtype, mode):
     rng = np.random.default_rng(7)
     p = W.make_random_profile(rng, 80, size_lo=1, size_hi=9000, P=4, grad_dtype=dtype)
@@ -179,7 +189,7 @@ def test_misaligned_sources_and_odd_sizes(dtype, mode):
     check_case(p, merged, mode, misalign=3, steps=2, label="misaligned")
 
 
-@pytest.mark.parametrize("mode", ["staged", "pipeline"])
+@pytest.mark.parametrize("mode", ["staged", "pipeline", "direct"])
 def test_thousands_of_one_element_tensors(mode):
     """More segments in one tile than the kernel stages in LDS, plus straddling vectors everywhere."""
     sizes = [1] * 3000 + [5, 1, 1, 7] * 50 + [4100, 3]
@@ -277,7 +287,8 @@ def test_results_do_not_depend_on_launch_shape(launch):
     rng = np.random.default_rng(77)
     p = W.make_random_profile(rng, 60, size_lo=1, size_hi=40000, P=8, allow_empty=True)
     merged = [0] + [int(x) for x in (rng.random(p.L - 1) < 0.5)]
-    for mode, resident in (("pipeline", 0), ("staged", 1 << 20), ("reduce_update", None), ("staged_per_group", 3 << 18)):
+    for mode, resident in (("pipeline", 0), ("staged", 1 << 20), ("reduce_update", None), ("staged_per_group", 3 << 18),
+                           ("direct", 1 << 19)):
         check_case(p, merged, mode, launch=launch, resident=resident, label=f"launch={launch}")
 
 
@@ -288,7 +299,8 @@ def test_results_do_not_depend_on_launch_shape(launch):
 @pytest.mark.parametrize("name,mode", [("resnet50", "pipeline"), ("resnet50", "staged"),
                                        ("tiny_layers", "pipeline"), ("tiny_layers", "staged_per_group"),
                                        ("vgg16", "pipeline"), ("vgg16", "staged"),
-                                       ("transformer", "pipeline"), ("transformer", "staged")])
+                                       ("transformer", "pipeline"), ("transformer", "staged"),
+                                       ("resnet50", "direct"), ("vgg16", "direct"), ("transformer", "direct")])
 def test_full_size_profiles(name, mode):
     p = W.make_profile(name)
     check_case(p, _plan_of(p), mode, steps=1)
@@ -561,7 +573,7 @@ def test_many_random_models(block):
         p = W.make_random_profile(rng, L, size_lo=1, size_hi=hi, P=P, grad_dtype=dtype, allow_empty=bool(rng.integers(0, 2)))
         merged = [0] + [int(x) for x in (rng.random(L - 1) < rng.choice([0.1, 0.5, 0.9]))]
         mode = str(rng.choice(["staged", "staged_per_group", "reduce_update", "pipeline", "pipeline_per_group",
-                               "pipeline_spans"]))
+                               "pipeline_spans", "direct", "direct_per_group_with_reduced"]))
         launch = (int(rng.choice([0, 1, 3])), bool(rng.integers(0, 2)), int(rng.choice([0, 1, 2, 5])))
         check_case(p, merged, mode, misalign=int(rng.choice([0, 0, 3, 5])), launch=launch,
                    resident=int(rng.choice([0, 1 << 16, 1 << 30])), seed=int(rng.integers(1, 10 ** 6)),
