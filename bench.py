@@ -12,6 +12,7 @@ Prints ONE JSON line.  `value` is algorithmic bytes of the path that ran divided
 from __future__ import annotations
 
 import argparse
+import dataclasses
 import json
 import os
 import statistics
@@ -41,6 +42,12 @@ def bytes_per_element(mode: str, P: int, g: int) -> int:
         return 2 * P * g + 16            # read P grads, write P merge, read+write w and v
     if mode == "direct":
         return P * g + 16                # read P grads, read+write w and v; no merge arenas
+    if mode == "pack":
+        return 2 * P * g
+    if mode == "reduce":
+        return P * g + 4
+    if mode == "unpack_update":
+        return 20
     if mode == "reduce_update":
         return 2 * P * g + (P * g + 16)  # pack, then merge -> w, v
     if mode in ("staged", "staged_per_group"):
@@ -50,7 +57,8 @@ def bytes_per_element(mode: str, P: int, g: int) -> int:
 
 def launches_per_step(mode: str, G: int) -> int:
     mode = mode[:-len("_graph")] if mode.endswith("_graph") else mode
-    return {"pipeline": 1, "pipeline_per_group": G, "direct": 1, "reduce_update": 2, "staged": 3, "staged_per_group": 3 * G}[mode]
+    return {"pipeline": 1, "pipeline_per_group": G, "direct": 1, "pack": 1, "reduce": 1, "unpack_update": 1,
+            "reduce_update": 2, "staged": 3, "staged_per_group": 3 * G}[mode]
 
 
 def run_step(dm, mode: str, lr: float, mu: float, G: int) -> None:
@@ -61,6 +69,12 @@ def run_step(dm, mode: str, lr: float, mu: float, G: int) -> None:
             dm.group_pipeline(lr, mu, k, write_reduced=False)
     elif mode == "direct":
         dm.direct_update(lr, mu, -1)
+    elif mode == "pack":
+        dm.pack(-1)
+    elif mode == "reduce":
+        dm.reduce(-1)
+    elif mode == "unpack_update":
+        dm.unpack_update(lr, mu, -1)
     elif mode == "reduce_update":
         dm.pack(-1); dm.reduce_update(lr, mu, -1)
     elif mode == "staged":
@@ -156,8 +170,11 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="resnet50")
     ap.add_argument("--mode", default="pipeline",
-                    choices=["pipeline", "pipeline_per_group", "direct", "reduce_update", "staged", "staged_per_group",
+                    choices=["pipeline", "pipeline_per_group", "direct", "pack", "reduce", "unpack_update",
+                             "reduce_update", "staged", "staged_per_group",
                              "pipeline_per_group_graph", "staged_per_group_graph"])
+    ap.add_argument("--workers", type=int, default=0,
+                    help="override the profile's worker count P (1 = the share one GPU of a data-parallel job holds)")
     ap.add_argument("--all-modes", action="store_true", help="also time the other launch modes (extra keys)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--blocks-per-cu", type=int, default=0)
@@ -204,6 +221,8 @@ def main() -> int:
         return 0
 
     p = W.make_profile(args.workload)
+    if args.workers > 0:
+        p = dataclasses.replace(p, P=args.workers)
     n = [int(x) for x in p.n_elems]
     g = p.elem_bytes
 
@@ -245,6 +264,9 @@ def main() -> int:
     dm.upload_weights(W.initial_weights_flat(p), W.initial_momentum_flat(p, zero=True))
     torch.cuda.synchronize()
 
+    dm.pack(-1); dm.reduce(-1)                  # so that modes that start mid-path read real data
+    torch.cuda.synchronize()
+
     E = p.total_elems
     tuned = None
     if args.tiles_per_workgroup < 0 and "per_group" not in args.mode:
@@ -282,7 +304,8 @@ def main() -> int:
                             "(Sec. 5.3) and calls the plan a one-time O(L^2) computation (Sec. 4.2)")
     if args.all_modes:
         others = {}
-        for mode in ("pipeline", "pipeline_per_group", "pipeline_per_group_graph", "direct", "reduce_update", "staged",
+        for mode in ("pipeline", "pipeline_per_group", "pipeline_per_group_graph", "direct", "pack", "reduce",
+                     "unpack_update", "reduce_update", "staged",
                      "staged_per_group", "staged_per_group_graph"):
             if mode == args.mode:
                 continue

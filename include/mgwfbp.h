@@ -14,7 +14,7 @@
  *        unpack_update  read the averaged gradient back out of the buffer and apply
  *                       v <- mu*v + g ; w <- w - eta*v to the per-layer tensors   (Eq. 2,
  *                       Algorithm 2 line 15; the momentum buffer is an addition of this library)
- *      plus two fused forms that produce bit-identical results with less memory traffic.
+ *      plus fused forms that produce bit-identical results with less memory traffic.
  *
  * Conventions
  *   - Tensor index i = 0..L-1 is the paper's layer l = i+1 (forward order).  Gradients become
