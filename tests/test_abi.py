@@ -2,6 +2,8 @@
 import ctypes
 import os
 import re
+import shutil
+import subprocess
 
 import pytest
 
@@ -54,3 +56,40 @@ def test_missing_library_fails_loudly(monkeypatch):
     monkeypatch.setattr(binding, "_LIB", None)
     with pytest.raises(M.MgwfbpError):
         M.plan([4], [1.0], 1.0, 1.0)
+
+
+@pytest.mark.skipif(shutil.which("gcc") is None, reason="gcc not available")
+def test_plain_c_client_links_and_agrees_with_the_oracle(tmp_path):
+    """include/mgwfbp.h compiles as strict C99 and a C program drives plan -> eval -> layout through the
+    shared library; its output is compared with the oracle's Algorithm 1, Eq. 8 and Sec. 5.3 layout."""
+    import numpy as np
+    from oracle import plan as OP
+    lib = M.library_path()
+    exe = str(tmp_path / "c_abi_client")
+    cmd = ["gcc", "-std=c99", "-pedantic", "-Wall", "-Wextra", "-Werror", "-I", os.path.join(ROOT, "include"),
+           os.path.join(ROOT, "tests", "c_abi_client.c"), "-o", exe, lib,
+           "-Wl,-rpath," + os.path.dirname(lib), "-Wl,-rpath,/opt/rocm/lib", "-Wl,--allow-shlib-undefined"]
+    r = subprocess.run(cmd, capture_output=True, text=True)
+    assert r.returncode == 0, r.stderr
+    rng = np.random.default_rng(5)
+    L = 40
+    sizes = [int(4 * x) for x in rng.integers(0, 5000, L)]
+    t_b = [float(x) for x in rng.uniform(1e-5, 3e-4, L)]
+    a, b = 5e-5, 2e-9
+    text = f"{L} {a!r} {b!r}\n" + "".join(f"{s} {t!r}\n" for s, t in zip(sizes, t_b))
+    r = subprocess.run([exe], input=text, capture_output=True, text=True, timeout=60)
+    assert r.returncode == 0, r.stderr
+    out = r.stdout.split("\n")
+    merged = OP.plan_algorithm1(sizes, t_b, a, b)
+    groups = OP.groups_in_arrival_order(merged)
+    assert 0 < sum(merged) < L - 1                               # the instance exercises both branches
+    assert out[0] == f"groups {len(groups)}"
+    assert float(out[1].split()[1]) == OP.iteration_time(merged, sizes, t_b, a, b)
+    assert [int(x.split()[2]) for x in out[2:2 + L]] == merged
+    grp, off, sizes_g = OP.merge_layout([s // 4 for s in sizes], merged)
+    for i in range(L):
+        assert out[2 + L + i] == f"tensor {i} group {grp[i]} off {off[i]}"
+    for k in range(len(groups)):
+        assert out[2 + 2 * L + k] == f"group {k} elems {sizes_g[k]}"
+    assert out[2 + 2 * L + len(groups)] == "device_call_on_host_ctx -1"
+    assert out[3 + 2 * L + len(groups)] == "negative_a -1"
