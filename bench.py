@@ -145,7 +145,7 @@ def cpu_baseline(profile, merged, bytes_per_step, budget_s=10.0):
     v = [x.copy() for x in W.split_by_layer(W.initial_momentum_flat(profile), profile.n_elems)]
     times = []
     t_all = time.perf_counter()
-    while not times or (time.perf_counter() - t_all < budget_s and len(times) < 20):
+    while not times or time.perf_counter() - t_all < budget_s:
         t0 = time.perf_counter()
         OD.merged_step(grads, groups, w, v, profile.lr, profile.momentum)
         times.append(time.perf_counter() - t0)
@@ -158,7 +158,8 @@ def cpu_baseline(profile, merged, bytes_per_step, budget_s=10.0):
         OP.plan_algorithm1(by, tb, profile.a, profile.b)
         plan_times.append((time.perf_counter() - t0) * 1e6)
     return {"plan_us": round(statistics.median(plan_times), 1), "value": bytes_per_step / best / 1e9, "unit": "GB/s", "cores": 1, "kind": "oracle",
-            "sample": f"{len(times)} full step(s) of the {profile.name} workload (all groups, P={profile.P}); "
+            "sample": f"{len(times)} full step(s) of the {profile.name} workload (all groups, P={profile.P}) in "
+                      f"{sum(times):.1f} s of CPU time; "
                       f"best {best * 1e3:.0f} ms/step; same byte count as `value`",
             "ms_per_step": best * 1e3, "host_cpus": os.cpu_count()}
 
