@@ -93,3 +93,21 @@ def test_plain_c_client_links_and_agrees_with_the_oracle(tmp_path):
         assert out[2 + 2 * L + k] == f"group {k} elems {sizes_g[k]}"
     assert out[2 + 2 * L + len(groups)] == "device_call_on_host_ctx -1"
     assert out[3 + 2 * L + len(groups)] == "negative_a -1"
+
+
+def test_product_code_never_touches_the_oracle():
+    """The oracle is test infrastructure: nothing in the package or its native sources may import, read or
+    mention it, and bench.py may use it only inside its CPU-baseline function."""
+    pkg = os.path.join(ROOT, "paper_1912_09268_amd")
+    for folder, _, files in os.walk(pkg):
+        for f in files:
+            if f.endswith((".py", ".cpp", ".hip", ".h")):
+                assert "oracle" not in open(os.path.join(folder, f)).read(), f
+    assert "oracle" not in open(os.path.join(ROOT, "include", "mgwfbp.h")).read()
+    gen = open(os.path.join(ROOT, "workloads.py")).read()          # shared input generators: no imports of either side
+    assert "import oracle" not in gen and "from oracle" not in gen and "paper_1912_09268_amd" not in gen
+    bench = open(os.path.join(ROOT, "bench.py")).read()
+    start = bench.index("def cpu_baseline")
+    end = bench.index("\ndef ", start + 1)
+    outside = bench[:start] + bench[end:]
+    assert "import oracle" not in outside and "from oracle" not in outside
