@@ -31,6 +31,8 @@ HBM_PEAK_GBPS = 8000.0
 MEASURED_TRAFFIC_BYTES = {
     ("resnet50", "pipeline"): 2.0466e9,
     ("vgg16", "pipeline"): 11.0736e9,
+    ("resnet50", "direct"): 1.2287e9,
+    ("vgg16", "direct"): 6.6498e9,
 }
 
 
