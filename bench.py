@@ -298,7 +298,7 @@ def main() -> int:
         "plan_us": round(plan_us, 2), "plan_us_through_python_binding": round(plan_us_binding, 2),
         "roofline": {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": round(achieved / HBM_PEAK_GBPS, 4),
-                     "traffic": MEASURED_TRAFFIC_BYTES.get((args.workload, args.mode)),
+                     "traffic": None if args.workers > 0 else MEASURED_TRAFFIC_BYTES.get((args.workload, args.mode)),
                      "kernel": f"mgwfbp_stream_kernel<{args.mode}>", "avg_launch_ms": round(kernel_ms, 5),
                      "algorithmic_bytes_per_launch": step_bytes // nl},
     }
