@@ -134,6 +134,16 @@ def autotune_launch(ctx, dm, mode, lr, mu, G, blocks_per_cu, xcd, candidates=(1,
     return best, seen
 
 
+def _cpu_model() -> str:
+    try:
+        for line in open("/proc/cpuinfo"):
+            if line.startswith("model name"):
+                return line.split(":", 1)[1].strip()
+    except OSError:
+        pass
+    return "unknown"
+
+
 def cpu_baseline(profile, merged, bytes_per_step, budget_s=10.0):
     """The oracle as it stands, timed on this host for whole steps until `budget_s` is used up."""
     import numpy as np
@@ -163,7 +173,7 @@ def cpu_baseline(profile, merged, bytes_per_step, budget_s=10.0):
             "sample": f"{len(times)} full step(s) of the {profile.name} workload (all groups, P={profile.P}) in "
                       f"{sum(times):.1f} s of CPU time; "
                       f"best {best * 1e3:.0f} ms/step; same byte count as `value`",
-            "ms_per_step": best * 1e3, "host_cpus": os.cpu_count()}
+            "ms_per_step": best * 1e3, "host_cpus": os.cpu_count(), "cpu_model": _cpu_model()}
 
 
 def main() -> int:
