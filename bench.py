@@ -27,10 +27,12 @@ HBM_PEAK_GBPS = 8000.0
 
 # HBM-side bytes per launch measured with rocprofv3 (--pmc FETCH_SIZE, then --pmc WRITE_SIZE, each scaled
 # by the same counter's reading for a plain 1 GiB device copy); the runs and the scale factors are in
-# profiles/mgwfbp_stream_kernel_<workload>_<mode>.txt.  Only the single-kernel mode has one figure.
+# profiles/mgwfbp_stream_kernel_<workload>_*.txt.  Only the single-kernel mode has one figure.
 MEASURED_TRAFFIC_BYTES = {
     ("resnet50", "pipeline"): 2.0466e9,
     ("vgg16", "pipeline"): 11.0736e9,
+    ("transformer", "pipeline"): 16.1089e9,
+    ("tiny_layers", "pipeline"): 1.8816e9,
     ("resnet50", "direct"): 1.2287e9,
     ("vgg16", "direct"): 6.6498e9,
 }
