@@ -13,7 +13,7 @@ from oracle import plan as OP
 pytestmark = pytest.mark.gpu
 
 MODES = ("staged", "staged_per_group", "reduce_update", "pipeline", "pipeline_per_group", "pipeline_no_reduced",
-         "pipeline_spans", "direct", "direct_per_group_with_reduced")
+         "pipeline_spans", "direct", "direct_per_group_with_reduced", "pipeline_two_streams")
 NO_REDUCED = ("reduce_update", "pipeline_no_reduced", "direct")
 NO_MERGE = ("direct", "direct_per_group_with_reduced")
 
@@ -52,6 +52,17 @@ def _run_mode(dm, mode, lr, mu, G):
             k += n
             width = width % 3 + 1
         dm.group_pipeline_span(lr, mu, G, 0)
+    elif mode == "pipeline_two_streams":          # groups touch disjoint elements: any streams, any overlap
+        import torch
+        main = torch.cuda.current_stream()
+        side = [torch.cuda.Stream(), torch.cuda.Stream()]       # default priority
+        for s in side:
+            s.wait_stream(main)
+        for k in range(G):
+            with torch.cuda.stream(side[k % 2]):
+                dm.group_pipeline(lr, mu, k)
+        for s in side:
+            main.wait_stream(s)
     elif mode == "direct":                        # merge arenas never written
         dm.direct_update(lr, mu)
     elif mode == "direct_per_group_with_reduced":
@@ -300,6 +311,7 @@ def test_results_do_not_depend_on_launch_shape(launch):
                                        ("tiny_layers", "pipeline"), ("tiny_layers", "staged_per_group"),
                                        ("vgg16", "pipeline"), ("vgg16", "staged"),
                                        ("transformer", "pipeline"), ("transformer", "staged"),
+                                       ("resnet50", "pipeline_two_streams"),
                                        ("resnet50", "direct"), ("vgg16", "direct"), ("transformer", "direct"),
                                        ("tiny_layers", "direct")])
 def test_full_size_profiles(name, mode):
