@@ -59,6 +59,39 @@ def bytes_per_element(mode: str, P: int, g: int) -> int:
     raise KeyError(mode)
 
 
+def stream_mix(mode: str, P: int):
+    """(read-only, write-only, updated-in-place) arrays a single-launch mode streams, or None."""
+    return {"pipeline": (P, P, 2), "direct": (P, 0, 2), "pack": (P, P, 0), "reduce": (P, 1, 0),
+            "unpack_update": (1, 0, 2)}.get(mode)
+
+
+def pattern_ceiling(mode: str, P: int, reps: int = 10):
+    """What the bare read/write mix of `mode` reaches on this GPU: mgwfbp_stream_probe over freshly allocated
+    binary32 arrays of 128 Mi elements each (for 16-bit gradients the stream counts are the same, the arrays
+    are not halved), timed with HIP events.  Returns GB/s, or None if the mix has no probe instance."""
+    import torch
+    import paper_1912_09268_amd as M
+    mix = stream_mix(mode, P)
+    if mix is None or mix[0] not in (0, 1, 2, 4, 8, 16) or mix[1] not in (0, 1, 2, 4, 8, 16):
+        return None
+    n = 128 << 20
+    tensors = [[torch.zeros(n, dtype=torch.float32, device="cuda") for _ in range(c)] for c in mix]
+    ptrs = [[t.data_ptr() for t in group] for group in tensors]
+    stream = int(torch.cuda.current_stream().cuda_stream)
+    for _ in range(2):
+        M.stream_probe(ptrs[0], ptrs[1], ptrs[2], n, stream)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(reps):
+        M.stream_probe(ptrs[0], ptrs[1], ptrs[2], n, stream)
+    e1.record()
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1) / reps
+    del tensors
+    return 4 * n * (mix[0] + mix[1] + 2 * mix[2]) / (ms * 1e-3) / 1e9
+
+
 def launches_per_step(mode: str, G: int) -> int:
     mode = mode[:-len("_graph")] if mode.endswith("_graph") else mode
     return {"pipeline": 1, "pipeline_per_group": G, "direct": 1, "pack": 1, "reduce": 1, "unpack_update": 1,
@@ -296,6 +329,9 @@ def main() -> int:
     kernel_ms = event_ms / nl
     achieved = (step_bytes / nl) / (kernel_ms * 1e-3) / 1e9
 
+    # what the same mix of read-only / write-only / updated streams reaches with nothing else in the kernel
+    ceiling = pattern_ceiling(args.mode, p.P)
+
     out = {
         "metric": "pack+reduce+unpack GB/s and % of HBM peak on 1 MI355X; plan time (us)",
         "value": round(value, 1), "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -309,6 +345,7 @@ def main() -> int:
         "pct_of_hbm_peak": round(100.0 * value / HBM_PEAK_GBPS, 2),
         "plan_us": round(plan_us, 2), "plan_us_through_python_binding": round(plan_us_binding, 2),
         "roofline": {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                     "bare_pattern_GBps": None if ceiling is None else round(ceiling, 1),
                      "frac": round(achieved / HBM_PEAK_GBPS, 4),
                      "traffic": None if args.workers > 0 else MEASURED_TRAFFIC_BYTES.get((args.workload, args.mode)),
                      "kernel": f"mgwfbp_stream_kernel<{args.mode}>", "avg_launch_ms": round(kernel_ms, 5),

@@ -285,6 +285,24 @@ int mgwfbp_group_pipeline_span(mgwfbp_ctx* ctx, int32_t group_first, int32_t gro
                                float lr, float momentum, void* hip_stream);
 
 /* ---------------------------------------------------------------------------------------------
+ * Measurement aid (not part of the method)
+ * ------------------------------------------------------------------------------------------- */
+
+/* Streams n_read read-only, n_write write-only and n_update updated-in-place binary32 device arrays of
+ * `elems` elements each through the GPU with the access shape of the pipeline kernels (one workgroup per
+ * 2048-element tile, 16-byte non-temporal accesses, all loads of a tile before its first store), so that
+ * a benchmark can report what the bare read/write mix of a mode reaches on the machine at hand:
+ *     write[i][e]  = read[i mod n_read][e]         (1.0f if n_read = 0)
+ *     update[j][e] = update[j][e] + sum_i read[i][e]
+ * read_ptrs / write_ptrs / update_ptrs are HOST arrays of device pointers (NULL allowed where the count
+ * is 0); the arrays must not overlap.  Counts: n_read, n_write in {0, 1, 2, 4, 8, 16}, n_update in
+ * {0, 1, 2}, not all zero; elems a positive multiple of 2048, 16-byte aligned arrays.  Asynchronous on
+ * hip_stream.  Errors: MGWFBP_EINVAL, MGWFBP_EHIP. */
+int mgwfbp_stream_probe(const float* const* read_ptrs, int32_t n_read, float* const* write_ptrs,
+                        int32_t n_write, float* const* update_ptrs, int32_t n_update, uint64_t elems,
+                        void* hip_stream);
+
+/* ---------------------------------------------------------------------------------------------
  * Diagnostics
  * ------------------------------------------------------------------------------------------- */
 int mgwfbp_last_hip_error(void);      /* hipError_t of the last failed HIP call on this thread, 0 if none */

@@ -46,6 +46,8 @@ _SIGNATURES = {
     "mgwfbp_fit_ab": (C.c_int, [_u64p, _f64p, C.c_int32, _f64p, _f64p]),
     "mgwfbp_simulate": (C.c_int, [_u64p, _f64p, C.c_int32, C.c_double, C.c_int32, C.c_double, C.c_double, C.c_double,
                                   _i32p, C.c_int32, _f64p, _f64p, _f64p, _i32p]),
+    "mgwfbp_stream_probe": (C.c_int, [C.POINTER(_vp), C.c_int32, C.POINTER(_vp), C.c_int32, C.POINTER(_vp), C.c_int32,
+                                      C.c_uint64, _vp]),
     "mgwfbp_ctx_create": (C.c_int, [C.POINTER(_vp), _u64p, C.c_int32, _u8p, C.c_int32, C.c_int32]),
     "mgwfbp_ctx_create_host": (C.c_int, [C.POINTER(_vp), _u64p, C.c_int32, _u8p, C.c_int32, C.c_int32]),
     "mgwfbp_ctx_destroy": (None, [_vp]),
@@ -184,6 +186,16 @@ def simulate(size_bytes: Sequence[int], t_backward_s: Sequence[float], t_forward
         float(beta_s_per_byte), float(gamma_s_per_byte), _ptr(wc, _i32p), n, _ptr(tw, _f64p), _ptr(ts, _f64p),
         _ptr(tm, _f64p), _ptr(g, _i32p)))
     return tw, ts, tm, g
+
+
+def stream_probe(read_ptrs: Sequence[int], write_ptrs: Sequence[int], update_ptrs: Sequence[int], elems: int,
+                 stream: int = 0) -> None:
+    """mgwfbp_stream_probe: the arguments are lists of device addresses of binary32 arrays of `elems` elements."""
+    def table(addrs):
+        return (_vp * max(len(addrs), 1))(*[int(a) for a in addrs]) if addrs else None
+    r, w, x = table(read_ptrs), table(write_ptrs), table(update_ptrs)
+    _check("mgwfbp_stream_probe", lib().mgwfbp_stream_probe(r, len(read_ptrs), w, len(write_ptrs), x, len(update_ptrs),
+                                                          int(elems), _vp(stream)))
 
 
 # --------------------------------------------------------------------------------------------

@@ -10,7 +10,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB_NAME = "libmgwfbp.so"
-SOURCES = ("plan.cpp", "model.cpp", "layout.cpp", "kernels.hip")
+SOURCES = ("plan.cpp", "model.cpp", "layout.cpp", "kernels.hip", "probe.hip")
 
 # -ffp-contract=off: the update and the reduction promise one rounding per operation.
 # The packed-fp32 feature is switched off for device code: packed single-precision instructions are

@@ -503,6 +503,8 @@ int note(hipError_t e) {
 
 }  // namespace
 
+int mgwfbp_note_hip_result(int hip_error_code) { return note(static_cast<hipError_t>(hip_error_code)); }
+
 // ---------------------------------------------------------------------------------------------
 // context
 // ---------------------------------------------------------------------------------------------

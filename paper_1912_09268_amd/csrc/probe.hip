@@ -1,0 +1,117 @@
+// A measurement aid, not part of the method: streams a chosen mix of read-only, write-only and
+// updated-in-place binary32 arrays through the GPU with the same access shape as the pipeline kernels
+// (one workgroup of 256 lanes per 2048-element tile, 16-byte non-temporal accesses, every load of a tile
+// issued before its first store).  bench.py uses it to report what the bare access pattern of a mode
+// reaches on the machine it runs on, next to what the real kernel reaches.
+#include <hip/hip_runtime.h>
+
+#include <cstdint>
+
+#include "mgwfbp.h"
+#include "tables.h"
+
+namespace {
+
+constexpr int PROBE_MAX = 16;
+constexpr int PROBE_TILE = 2048;
+constexpr int PROBE_BLOCK = 256;
+
+typedef float pf4 __attribute__((ext_vector_type(4)));
+#define PROBE_GLOBAL __attribute__((address_space(1)))
+
+struct ProbePtrs {
+    const float* r[PROBE_MAX];
+    float* w[PROBE_MAX];
+    float* x[PROBE_MAX];
+};
+
+template <int R, int W, int X>
+__global__ void __launch_bounds__(PROBE_BLOCK) mgwfbp_probe_kernel(const ProbePtrs P) {
+    const int64_t base = static_cast<int64_t>(blockIdx.x) * PROBE_TILE + threadIdx.x * 4;
+    pf4 a[2][R > 0 ? R : 1], xv[2][X > 0 ? X : 1];
+#pragma unroll
+    for (int u = 0; u < 2; ++u) {
+#pragma unroll
+        for (int i = 0; i < R; ++i)
+            a[u][i] = __builtin_nontemporal_load((const PROBE_GLOBAL pf4*)(P.r[i] + base + u * 1024));
+#pragma unroll
+        for (int i = 0; i < X; ++i)
+            xv[u][i] = __builtin_nontemporal_load((const PROBE_GLOBAL pf4*)(P.x[i] + base + u * 1024));
+    }
+#pragma unroll
+    for (int u = 0; u < 2; ++u) {
+        pf4 s = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int i = 0; i < R; ++i) s = s + a[u][i];
+#pragma unroll
+        for (int i = 0; i < W; ++i) {
+            pf4 val = {1.f, 1.f, 1.f, 1.f};
+            if constexpr (R > 0) val = a[u][i % (R > 0 ? R : 1)];
+            __builtin_nontemporal_store(val, (PROBE_GLOBAL pf4*)(P.w[i] + base + u * 1024));
+        }
+#pragma unroll
+        for (int i = 0; i < X; ++i)
+            __builtin_nontemporal_store(xv[u][i] + s, (PROBE_GLOBAL pf4*)(P.x[i] + base + u * 1024));
+        if constexpr (X == 0 && R > 0) {
+            // nothing consumes the sum of the inputs in this mix: an empty asm statement does, so that every
+            // read-only array is really read
+            asm volatile("" ::"v"(s[0]), "v"(s[1]), "v"(s[2]), "v"(s[3]));
+        }
+    }
+}
+
+template <int R, int W, int X>
+int probe_launch(const ProbePtrs& P, uint64_t tiles, hipStream_t stream) {
+    hipLaunchKernelGGL((mgwfbp_probe_kernel<R, W, X>), dim3(static_cast<unsigned>(tiles)), dim3(PROBE_BLOCK), 0,
+                       stream, P);
+    return mgwfbp_note_hip_result(static_cast<int>(hipGetLastError()));
+}
+
+template <int R, int W>
+int probe_by_x(int x, const ProbePtrs& P, uint64_t tiles, hipStream_t s) {
+    switch (x) {
+        case 0: return probe_launch<R, W, 0>(P, tiles, s);
+        case 1: return probe_launch<R, W, 1>(P, tiles, s);
+        case 2: return probe_launch<R, W, 2>(P, tiles, s);
+        default: return MGWFBP_EINVAL;
+    }
+}
+
+template <int R>
+int probe_by_w(int w, int x, const ProbePtrs& P, uint64_t tiles, hipStream_t s) {
+    switch (w) {
+        case 0: return probe_by_x<R, 0>(x, P, tiles, s);
+        case 1: return probe_by_x<R, 1>(x, P, tiles, s);
+        case 2: return probe_by_x<R, 2>(x, P, tiles, s);
+        case 4: return probe_by_x<R, 4>(x, P, tiles, s);
+        case 8: return probe_by_x<R, 8>(x, P, tiles, s);
+        case 16: return probe_by_x<R, 16>(x, P, tiles, s);
+        default: return MGWFBP_EINVAL;
+    }
+}
+
+}  // namespace
+
+extern "C" int mgwfbp_stream_probe(const float* const* read_ptrs, int32_t n_read, float* const* write_ptrs,
+                                   int32_t n_write, float* const* update_ptrs, int32_t n_update, uint64_t elems,
+                                   void* hip_stream) {
+    if (n_read < 0 || n_write < 0 || n_update < 0 || n_read + n_write + n_update == 0) return MGWFBP_EINVAL;
+    if (n_read > PROBE_MAX || n_write > PROBE_MAX || n_update > PROBE_MAX) return MGWFBP_EINVAL;
+    if ((n_read && !read_ptrs) || (n_write && !write_ptrs) || (n_update && !update_ptrs)) return MGWFBP_EINVAL;
+    if (elems == 0 || elems % PROBE_TILE != 0 || elems / PROBE_TILE > 0x7fffffffull) return MGWFBP_EINVAL;
+    ProbePtrs P = {};
+    for (int i = 0; i < n_read; ++i) if ((P.r[i] = read_ptrs[i]) == nullptr) return MGWFBP_EINVAL;
+    for (int i = 0; i < n_write; ++i) if ((P.w[i] = write_ptrs[i]) == nullptr) return MGWFBP_EINVAL;
+    for (int i = 0; i < n_update; ++i) if ((P.x[i] = update_ptrs[i]) == nullptr) return MGWFBP_EINVAL;
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    const uint64_t tiles = elems / PROBE_TILE;
+    switch (n_read) {
+        case 0: return probe_by_w<0>(n_write, n_update, P, tiles, s);
+        case 1: return probe_by_w<1>(n_write, n_update, P, tiles, s);
+        case 2: return probe_by_w<2>(n_write, n_update, P, tiles, s);
+        case 4: return probe_by_w<4>(n_write, n_update, P, tiles, s);
+        case 8: return probe_by_w<8>(n_write, n_update, P, tiles, s);
+        case 16: return probe_by_w<16>(n_write, n_update, P, tiles, s);
+        default: return MGWFBP_EINVAL;
+    }
+}

@@ -55,6 +55,10 @@ struct HostTables {
     std::vector<TileHdr> tiles;           // [T]
 };
 
+// Records a failed HIP call for mgwfbp_last_hip_error() on this thread and returns MGWFBP_EHIP; returns
+// MGWFBP_OK for code 0 (hipSuccess).  Defined next to the device entry points.
+int mgwfbp_note_hip_result(int hip_error_code);
+
 // Returns 0 or a negative mgwfbp_status.  Pure host code.
 int mgwfbp_build_tables(const uint64_t* n_elems, int32_t L, const uint8_t* merged, HostTables& out);
 

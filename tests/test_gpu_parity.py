@@ -592,3 +592,42 @@ def test_many_random_models(block):
         check_case(p, merged, mode, misalign=int(rng.choice([0, 0, 3, 5])), launch=launch,
                    resident=int(rng.choice([0, 1 << 16, 1 << 30])), seed=int(rng.integers(1, 10 ** 6)),
                    label=f"random block {block} case {case}")
+
+
+# ------------------------------------------------------------------------------------------
+# the measurement aid does what its header says (so that the ceilings bench.py reports mean something)
+# ------------------------------------------------------------------------------------------
+
+@pytest.mark.parametrize("mix", [(1, 0, 0), (8, 0, 0), (0, 1, 0), (1, 1, 0), (2, 4, 1), (8, 8, 2), (8, 0, 2),
+                                 (16, 16, 2), (0, 2, 2), (0, 0, 1)])
+def test_stream_probe_moves_what_it_says(mix):
+    import torch
+    import paper_1912_09268_amd as M
+    r, w, x = mix
+    n = 5 * 2048
+    rng = np.random.default_rng(r * 100 + w * 10 + x)
+    host = [[rng.standard_normal(n).astype(np.float32) for _ in range(c)] for c in mix]
+    dev = [[torch.from_numpy(a).cuda() for a in group] for group in host]
+    _say(f"[probe] mix={mix} n={n}")
+    M.stream_probe(*[[t.data_ptr() for t in group] for group in dev], n, int(torch.cuda.current_stream().cuda_stream))
+    torch.cuda.synchronize()
+    s = np.zeros(n, np.float32)
+    for a in host[0]:
+        s = s + a                                      # binary32, in array order, as the kernel adds
+    for i in range(r):
+        assert np.array_equal(dev[0][i].cpu().numpy(), host[0][i]), "inputs must not change"
+    for i in range(w):
+        want = host[0][i % r] if r else np.ones(n, np.float32)
+        assert np.array_equal(dev[1][i].cpu().numpy(), want)
+    for j in range(x):
+        assert np.array_equal(dev[2][j].cpu().numpy(), host[2][j] + s)
+
+
+def test_stream_probe_rejects_what_it_cannot_run():
+    import torch
+    import paper_1912_09268_amd as M
+    t = torch.zeros(4096, dtype=torch.float32, device="cuda")
+    for args in (([], [], [], 2048), ([t.data_ptr()] * 3, [], [], 2048), ([t.data_ptr()], [], [], 1000),
+                 ([t.data_ptr()], [], [], 0), ([0], [], [], 2048), ([], [], [t.data_ptr()] * 3, 2048)):
+        with pytest.raises(M.MgwfbpError):
+            M.stream_probe(*args)
