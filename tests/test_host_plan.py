@@ -113,6 +113,18 @@ def test_plan_opt_matches_oracle_and_exhaustive_search():
         assert t <= M.eval_plan(greedy, p.size_bytes, p.t_backward, p.a, p.b)
 
 
+def test_library_plans_against_exhaustive_search_at_sixteen_layers():
+    rng = np.random.default_rng(316)
+    p = W.make_random_profile(rng, 16, size_hi=10 ** 6)
+    by, tb = _lists(p)
+    t_bf, _ = OP.bruteforce_best(by, tb, p.a, p.b)
+    merged, _, t = M.plan_opt(p.size_bytes, p.t_backward, p.a, p.b)
+    assert t == t_bf
+    greedy, _ = M.plan(p.size_bytes, p.t_backward, p.a, p.b)
+    assert greedy.tolist() == OP.plan_algorithm1(by, tb, p.a, p.b)
+    assert t_bf <= M.eval_plan(greedy, p.size_bytes, p.t_backward, p.a, p.b)
+
+
 @pytest.mark.parametrize("name", W.PROFILE_NAMES)
 def test_plan_opt_on_profiles(name, capsys):
     p = W.make_profile(name)

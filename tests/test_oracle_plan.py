@@ -376,6 +376,26 @@ def test_plan_optimal_equals_exhaustive_minimum():
         assert OP.iteration_time(m_dp, by, tb, a, b) == t_dp        # the returned plan attains it
 
 
+@pytest.mark.parametrize("L", [14, 15, 16])
+def test_exhaustive_search_up_to_sixteen_layers(L):
+    """All 2^(L-1) plans at the largest sizes the exhaustive check is asked for: the dynamic programme attains
+    the minimum bit for bit, Algorithm 1 is never better than it and never worse than wait-free
+    backpropagation, and neither baseline beats the minimum."""
+    rng = np.random.default_rng(300 + L)
+    for trial in range(2):
+        by, tb, a, b = _rand_instance(rng, L, size_hi=10 ** 6 if trial else 5000)
+        t_bf, m_bf = OP.bruteforce_best(by, tb, a, b)
+        assert sum(1 for _ in OP.all_plans(L)) == 2 ** (L - 1)
+        t_dp, m_dp = OP.plan_optimal(by, tb, a, b)
+        assert t_dp == t_bf and OP.iteration_time(m_dp, by, tb, a, b) == t_bf
+        t_g = OP.iteration_time(OP.plan_algorithm1(by, tb, a, b), by, tb, a, b)
+        t_w, t_s = OP.wfbp_time(by, tb, a, b), OP.single_layer_time(by, tb, a, b)
+        tol = 1e-12 * max(t_w, t_s)
+        assert t_bf <= t_g + tol and t_g <= t_w + tol and t_bf <= min(t_w, t_s) + tol
+        groups = OP.groups_in_arrival_order(m_bf)                     # contiguous, cover every layer once
+        assert [i for g in groups for i in g] == list(range(L - 1, -1, -1))
+
+
 def test_plan_optimal_on_hand_example_and_wide_ranges():
     t, m = OP.plan_optimal(HAND_BYTES, HAND_TB, 1.0, 1.0)
     assert m == [0, 1, 0] and t == pytest.approx(102.0)
