@@ -87,11 +87,11 @@ def stream_mix(mode: str, P: int):
 
 
 def pattern_ceiling(mode: str, P: int, reps: int = 10):
-    """What the bare read/write mix of `mode` reaches on this GPU: mgwfbp_stream_probe over freshly allocated
+    """What the bare read/write mix of `mode` reaches on this GPU: bench_aid_stream_probe over freshly allocated
     binary32 arrays of 128 Mi elements each (for 16-bit gradients the stream counts are the same, the arrays
     are not halved), timed with HIP events.  Returns GB/s, or None if the mix has no probe instance."""
     import torch
-    import paper_1912_09268_amd as M
+    import bench_aid as A
     mix = stream_mix(mode, P)
     if mix is None or mix[0] not in (0, 1, 2, 4, 8, 16) or mix[1] not in (0, 1, 2, 4, 8, 16):
         return None
@@ -100,12 +100,12 @@ def pattern_ceiling(mode: str, P: int, reps: int = 10):
     ptrs = [[t.data_ptr() for t in group] for group in tensors]
     stream = int(torch.cuda.current_stream().cuda_stream)
     for _ in range(2):
-        M.stream_probe(ptrs[0], ptrs[1], ptrs[2], n, stream)
+        A.stream_probe(ptrs[0], ptrs[1], ptrs[2], n, stream)
     torch.cuda.synchronize()
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     e0.record()
     for _ in range(reps):
-        M.stream_probe(ptrs[0], ptrs[1], ptrs[2], n, stream)
+        A.stream_probe(ptrs[0], ptrs[1], ptrs[2], n, stream)
     e1.record()
     torch.cuda.synchronize()
     ms = e0.elapsed_time(e1) / reps

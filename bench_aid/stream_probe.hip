@@ -1,14 +1,19 @@
-// A measurement aid, not part of the method: streams a chosen mix of read-only, write-only and
-// updated-in-place binary32 arrays through the GPU with the same access shape as the pipeline kernels
-// (one workgroup of 256 lanes per 2048-element tile, 16-byte non-temporal accesses, every load of a tile
-// issued before its first store).  bench.py uses it to report what the bare access pattern of a mode
-// reaches on the machine it runs on, next to what the real kernel reaches.
+// The benchmark's measurement aid, built into its own shared object: not part of the MG-WFBP library and not
+// part of the method.
+//   bench_aid_stream_probe  streams a chosen mix of read-only, write-only and updated-in-place binary32
+//                           arrays through the GPU with the access shape of the pipeline kernels (one workgroup
+//                           of 256 lanes per 2048-element tile, 16-byte non-temporal accesses, every load of a
+//                           tile issued before its first store), so that bench.py can report what the bare
+//                           access pattern of a mode reaches next to what the real kernel reaches;
+//   bench_aid_cache_scrub   displaces the contents of the memory-side cache between timed steps.
 #include <hip/hip_runtime.h>
 
 #include <cstdint>
 
-#include "mgwfbp.h"
-#include "tables.h"
+#include "stream_probe.h"
+
+#define AID_EINVAL (-1)
+#define AID_EHIP (-3)
 
 namespace {
 
@@ -26,7 +31,7 @@ struct ProbePtrs {
 };
 
 template <int R, int W, int X>
-__global__ void __launch_bounds__(PROBE_BLOCK) mgwfbp_probe_kernel(const ProbePtrs P) {
+__global__ void __launch_bounds__(PROBE_BLOCK) bench_aid_probe_kernel(const ProbePtrs P) {
     const int64_t base = static_cast<int64_t>(blockIdx.x) * PROBE_TILE + threadIdx.x * 4;
     pf4 a[2][R > 0 ? R : 1], xv[2][X > 0 ? X : 1];
 #pragma unroll
@@ -62,9 +67,9 @@ __global__ void __launch_bounds__(PROBE_BLOCK) mgwfbp_probe_kernel(const ProbePt
 
 template <int R, int W, int X>
 int probe_launch(const ProbePtrs& P, uint64_t tiles, hipStream_t stream) {
-    hipLaunchKernelGGL((mgwfbp_probe_kernel<R, W, X>), dim3(static_cast<unsigned>(tiles)), dim3(PROBE_BLOCK), 0,
+    hipLaunchKernelGGL((bench_aid_probe_kernel<R, W, X>), dim3(static_cast<unsigned>(tiles)), dim3(PROBE_BLOCK), 0,
                        stream, P);
-    return mgwfbp_note_hip_result(static_cast<int>(hipGetLastError()));
+    return hipGetLastError() == hipSuccess ? 0 : AID_EHIP;
 }
 
 template <int R, int W>
@@ -73,7 +78,7 @@ int probe_by_x(int x, const ProbePtrs& P, uint64_t tiles, hipStream_t s) {
         case 0: return probe_launch<R, W, 0>(P, tiles, s);
         case 1: return probe_launch<R, W, 1>(P, tiles, s);
         case 2: return probe_launch<R, W, 2>(P, tiles, s);
-        default: return MGWFBP_EINVAL;
+        default: return AID_EINVAL;
     }
 }
 
@@ -86,23 +91,43 @@ int probe_by_w(int w, int x, const ProbePtrs& P, uint64_t tiles, hipStream_t s) 
         case 4: return probe_by_x<R, 4>(x, P, tiles, s);
         case 8: return probe_by_x<R, 8>(x, P, tiles, s);
         case 16: return probe_by_x<R, 16>(x, P, tiles, s);
-        default: return MGWFBP_EINVAL;
+        default: return AID_EINVAL;
     }
+}
+
+// first half -> second half, ordinary (cacheable) 16-byte accesses; one workgroup per 2048 elements
+__global__ void __launch_bounds__(PROBE_BLOCK) bench_aid_scrub_kernel(const pf4* src, pf4* dst) {
+    const int64_t v = static_cast<int64_t>(blockIdx.x) * (PROBE_TILE / 4) + threadIdx.x;
+    const pf4 a = src[v], b = src[v + PROBE_BLOCK];
+    dst[v] = a;
+    dst[v + PROBE_BLOCK] = b;
 }
 
 }  // namespace
 
-extern "C" int mgwfbp_stream_probe(const float* const* read_ptrs, int32_t n_read, float* const* write_ptrs,
+extern "C" int bench_aid_cache_scrub(void* buf, uint64_t bytes, void* hip_stream) {
+    const uint64_t half = bytes / 2;
+    if (buf == nullptr || bytes == 0 || half % (PROBE_TILE * sizeof(float)) != 0 ||
+        (reinterpret_cast<uintptr_t>(buf) & 15u) != 0 || half / (PROBE_TILE * sizeof(float)) > 0x7fffffffull)
+        return AID_EINVAL;
+    const unsigned tiles = static_cast<unsigned>(half / (PROBE_TILE * sizeof(float)));
+    hipLaunchKernelGGL(bench_aid_scrub_kernel, dim3(tiles), dim3(PROBE_BLOCK), 0, static_cast<hipStream_t>(hip_stream),
+                       reinterpret_cast<const pf4*>(buf),
+                       reinterpret_cast<pf4*>(static_cast<char*>(buf) + half));
+    return hipGetLastError() == hipSuccess ? 0 : AID_EHIP;
+}
+
+extern "C" int bench_aid_stream_probe(const float* const* read_ptrs, int32_t n_read, float* const* write_ptrs,
                                    int32_t n_write, float* const* update_ptrs, int32_t n_update, uint64_t elems,
                                    void* hip_stream) {
-    if (n_read < 0 || n_write < 0 || n_update < 0 || n_read + n_write + n_update == 0) return MGWFBP_EINVAL;
-    if (n_read > PROBE_MAX || n_write > PROBE_MAX || n_update > PROBE_MAX) return MGWFBP_EINVAL;
-    if ((n_read && !read_ptrs) || (n_write && !write_ptrs) || (n_update && !update_ptrs)) return MGWFBP_EINVAL;
-    if (elems == 0 || elems % PROBE_TILE != 0 || elems / PROBE_TILE > 0x7fffffffull) return MGWFBP_EINVAL;
+    if (n_read < 0 || n_write < 0 || n_update < 0 || n_read + n_write + n_update == 0) return AID_EINVAL;
+    if (n_read > PROBE_MAX || n_write > PROBE_MAX || n_update > PROBE_MAX) return AID_EINVAL;
+    if ((n_read && !read_ptrs) || (n_write && !write_ptrs) || (n_update && !update_ptrs)) return AID_EINVAL;
+    if (elems == 0 || elems % PROBE_TILE != 0 || elems / PROBE_TILE > 0x7fffffffull) return AID_EINVAL;
     ProbePtrs P = {};
-    for (int i = 0; i < n_read; ++i) if ((P.r[i] = read_ptrs[i]) == nullptr) return MGWFBP_EINVAL;
-    for (int i = 0; i < n_write; ++i) if ((P.w[i] = write_ptrs[i]) == nullptr) return MGWFBP_EINVAL;
-    for (int i = 0; i < n_update; ++i) if ((P.x[i] = update_ptrs[i]) == nullptr) return MGWFBP_EINVAL;
+    for (int i = 0; i < n_read; ++i) if ((P.r[i] = read_ptrs[i]) == nullptr) return AID_EINVAL;
+    for (int i = 0; i < n_write; ++i) if ((P.w[i] = write_ptrs[i]) == nullptr) return AID_EINVAL;
+    for (int i = 0; i < n_update; ++i) if ((P.x[i] = update_ptrs[i]) == nullptr) return AID_EINVAL;
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
     const uint64_t tiles = elems / PROBE_TILE;
     switch (n_read) {
@@ -112,6 +137,6 @@ extern "C" int mgwfbp_stream_probe(const float* const* read_ptrs, int32_t n_read
         case 4: return probe_by_w<4>(n_write, n_update, P, tiles, s);
         case 8: return probe_by_w<8>(n_write, n_update, P, tiles, s);
         case 16: return probe_by_w<16>(n_write, n_update, P, tiles, s);
-        default: return MGWFBP_EINVAL;
+        default: return AID_EINVAL;
     }
 }

@@ -56,7 +56,8 @@ typedef enum mgwfbp_status {
     MGWFBP_OK = 0,
     MGWFBP_EINVAL = -1, /* null pointer, size or index out of range, non-finite or negative time */
     MGWFBP_ENOMEM = -2, /* host or device allocation failed                                       */
-    MGWFBP_EHIP = -3    /* a HIP runtime call failed; see mgwfbp_last_hip_error()                 */
+    MGWFBP_EHIP = -3,   /* a HIP runtime call failed; see mgwfbp_last_hip_error()                 */
+    MGWFBP_ECAPACITY = -4 /* the model needs larger tables than a fixed-size entry point can hold         */
 } mgwfbp_status;
 
 typedef enum mgwfbp_dtype {
@@ -107,6 +108,16 @@ int mgwfbp_plan_opt(const uint64_t* size_bytes, const double* t_backward_s, int3
  * down) and Eq. 14 (start of the lower layer).  merged[0] must be 0.  Result in *t_iter_out. */
 int mgwfbp_eval(const uint8_t* merged, const uint64_t* size_bytes, const double* t_backward_s,
                 int32_t L, double a_s, double b_s_per_byte, double* t_iter_out);
+
+/* When each group's merge buffer is full, measured from the start of the backward pass: a buffer is full
+ * (Sec. 5.3; Algorithm 2's handler sends it) once the gradient of the group's lowest layer exists, which is
+ * at tau_b + t_b of that layer with tau_b from Eq. 6 and tau_b of the last layer = 0 as in Algorithm 1.
+ *   merged, t_backward_s  host [L]   as for mgwfbp_eval
+ *   ready_out             host [G] or NULL   out: seconds, group 0 (the first to fill) first; non-decreasing
+ *   n_groups_out          host [1] or NULL   out: G
+ * Errors: MGWFBP_EINVAL. */
+int mgwfbp_group_ready_times(const uint8_t* merged, const double* t_backward_s, int32_t L,
+                             double* ready_out, int32_t* n_groups_out);
 
 /* ---------------------------------------------------------------------------------------------
  * Host: where a and b come from, and the worker-count sweep
@@ -201,15 +212,21 @@ int mgwfbp_ctx_tables(const mgwfbp_ctx* ctx, int32_t* n_segments, void* tiles_ou
  *                            over the work; <= 0 restores the default
  *   xcd_contiguous != 0      renumbers workgroups so that each of the 8 accelerator dies walks one
  *                            contiguous eighth of the range instead of every eighth piece
- *   tiles_per_workgroup > 0  consecutive tiles a workgroup handles per turn; <= 0 restores the default */
+ *   tiles_per_workgroup > 0  consecutive tiles a workgroup handles per turn; with 2 (4) or more, two (four)
+ *                            consecutive full tiles of one tensor are taken together as one longer chunk;
+ *                            <= 0 restores the default
+ * Results never depend on the launch shape. */
 int mgwfbp_ctx_set_launch(mgwfbp_ctx* ctx, int32_t blocks_per_cu, int32_t xcd_contiguous,
                           int32_t tiles_per_workgroup);
 
 /* How many bytes of weights + momenta (8 per element, counted from the start of the arena) are accessed
  * with ordinary loads and stores so that they stay in the GPU's 256 MB memory-side cache from one
  * iteration to the next; the rest of w and v is streamed with non-temporal accesses like the gradients.
- * Results do not depend on it.  Default 232 MiB; 0 streams everything.  Synchronous (re-uploads the tile
- * table); do not call while kernels of this context are in flight. */
+ * Results do not depend on it.  Default 0 (everything is streamed: in a training loop a forward and a backward
+ * pass run between two updates, so nothing would survive in that cache anyway); a caller whose next reader of
+ * the weights comes soon may set up to about 232 MiB.  Synchronous: the tile table is rewritten with a blocking
+ * copy, so the call is allowed only while no kernel launched with this context is still in flight (synchronise
+ * the streams it was used on first). */
 int mgwfbp_ctx_set_resident_bytes(mgwfbp_ctx* ctx, uint64_t bytes);
 
 /* ---------------------------------------------------------------------------------------------
@@ -284,23 +301,27 @@ int mgwfbp_group_pipeline_span(mgwfbp_ctx* ctx, int32_t group_first, int32_t gro
                                float* const* d_w_ptrs, float* const* d_v_ptrs,
                                float lr, float momentum, void* hip_stream);
 
-/* ---------------------------------------------------------------------------------------------
- * Measurement aid (not part of the method)
- * ------------------------------------------------------------------------------------------- */
-
-/* Streams n_read read-only, n_write write-only and n_update updated-in-place binary32 device arrays of
- * `elems` elements each through the GPU with the access shape of the pipeline kernels (one workgroup per
- * 2048-element tile, 16-byte non-temporal accesses, all loads of a tile before its first store), so that
- * a benchmark can report what the bare read/write mix of a mode reaches on the machine at hand:
- *     write[i][e]  = read[i mod n_read][e]         (1.0f if n_read = 0)
- *     update[j][e] = update[j][e] + sum_i read[i][e]
- * read_ptrs / write_ptrs / update_ptrs are HOST arrays of device pointers (NULL allowed where the count
- * is 0); the arrays must not overlap.  Counts: n_read, n_write in {0, 1, 2, 4, 8, 16}, n_update in
- * {0, 1, 2}, not all zero; elems a positive multiple of 2048, 16-byte aligned arrays.  Asynchronous on
- * hip_stream.  Errors: MGWFBP_EINVAL, MGWFBP_EHIP. */
-int mgwfbp_stream_probe(const float* const* read_ptrs, int32_t n_read, float* const* write_ptrs,
-                        int32_t n_write, float* const* update_ptrs, int32_t n_update, uint64_t elems,
-                        void* hip_stream);
+/* Algorithm 2's communication handler, driven by a recorded schedule instead of a live backward pass.
+ * Group k's buffer counts as full at host time t0 + time_scale * group_ready_s[k], t0 being the moment of the
+ * call.  The handler waits (spinning on the host's monotonic clock) until the next unlaunched group is full,
+ * issues ONE fused pack + reduce + update launch (as mgwfbp_group_pipeline_span) covering every group that is
+ * full by then, on the next of `streams` in round-robin order, and repeats until all groups are launched; then
+ * it waits for all the streams.  Groups that fill while the handler is busy launching are therefore batched
+ * into the next launch, and a schedule faster than the launch rate degenerates into few, long launches.
+ * Unlike the other device entry points this call BLOCKS until the work is done.
+ *   group_ready_s  host [G]   e.g. from mgwfbp_group_ready_times; finite, >= 0, non-decreasing
+ *   time_scale     >= 0; 1 replays the schedule in real time, 0 makes every group full at once
+ *   streams        host [n_streams] of hipStream_t, 1 <= n_streams <= 16, all of default priority; launches for
+ *                  different groups touch disjoint elements, so they need no ordering among themselves
+ *   stats_out      host [4] or NULL  out: [0] launches issued, [1] seconds from t0 at which the last group was
+ *                  full, [2] seconds from t0 at which every stream had drained, [3] = [2] - [1], the part of
+ *                  the pipeline left exposed after the last gradient
+ * Errors: MGWFBP_EINVAL, MGWFBP_EHIP. */
+int mgwfbp_handler_replay(mgwfbp_ctx* ctx, const double* group_ready_s, double time_scale,
+                          void* const* streams, int32_t n_streams,
+                          const void* const* d_grad_ptrs, void* const* d_merge_bufs, float* d_reduced,
+                          float* const* d_w_ptrs, float* const* d_v_ptrs, float lr, float momentum,
+                          double* stats_out);
 
 /* ---------------------------------------------------------------------------------------------
  * Diagnostics

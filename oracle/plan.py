@@ -249,6 +249,21 @@ def groups_in_arrival_order(merged: Sequence[int]) -> List[List[int]]:
     return groups
 
 
+def group_ready_times(merged: Sequence[int], t_backward: Sequence[float]) -> List[float]:
+    """When each group's buffer is full, in seconds from the start of the backward pass, first group first.
+
+    The handler of Algorithm 2 sends a buffer when the layer it has just pushed is normal; that layer's
+    gradient exists at tau_b^(l) + t_b^(l) (Eq. 6 with tau_b^(L) = 0)."""
+    L = len(merged)
+    t_b1 = _one_based(float(x) for x in t_backward)
+    tau_b = backward_start_times(t_b1) if L else []
+    ready = []
+    for members in groups_in_arrival_order(merged):
+        l = members[-1] + 1                      # the group's last arrival, a normal layer
+        ready.append(tau_b[l] + t_b1[l])
+    return ready
+
+
 def merge_layout(n_elems: Sequence[int], merged: Sequence[int]):
     """Element layout of the pre-allocated merge buffers (Sec. 5.3).
 

@@ -16,7 +16,7 @@ BF16 = 1
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB: Optional[C.CDLL] = None
 
-_STATUS = {0: "MGWFBP_OK", -1: "MGWFBP_EINVAL", -2: "MGWFBP_ENOMEM", -3: "MGWFBP_EHIP"}
+_STATUS = {0: "MGWFBP_OK", -1: "MGWFBP_EINVAL", -2: "MGWFBP_ENOMEM", -3: "MGWFBP_EHIP", -4: "MGWFBP_ECAPACITY"}
 
 
 class MgwfbpError(RuntimeError):
@@ -42,12 +42,11 @@ _SIGNATURES = {
     "mgwfbp_plan": (C.c_int, [_u64p, _f64p, C.c_int32, C.c_double, C.c_double, _u8p, _i32p, _i32p]),
     "mgwfbp_plan_opt": (C.c_int, [_u64p, _f64p, C.c_int32, C.c_double, C.c_double, _u8p, _i32p, _i32p, _f64p]),
     "mgwfbp_eval": (C.c_int, [_u8p, _u64p, _f64p, C.c_int32, C.c_double, C.c_double, _f64p]),
+    "mgwfbp_group_ready_times": (C.c_int, [_u8p, _f64p, C.c_int32, _f64p, _i32p]),
     "mgwfbp_allreduce_ab": (C.c_int, [C.c_int32, C.c_int32, C.c_double, C.c_double, C.c_double, _f64p, _f64p]),
     "mgwfbp_fit_ab": (C.c_int, [_u64p, _f64p, C.c_int32, _f64p, _f64p]),
     "mgwfbp_simulate": (C.c_int, [_u64p, _f64p, C.c_int32, C.c_double, C.c_int32, C.c_double, C.c_double, C.c_double,
                                   _i32p, C.c_int32, _f64p, _f64p, _f64p, _i32p]),
-    "mgwfbp_stream_probe": (C.c_int, [C.POINTER(_vp), C.c_int32, C.POINTER(_vp), C.c_int32, C.POINTER(_vp), C.c_int32,
-                                      C.c_uint64, _vp]),
     "mgwfbp_ctx_create": (C.c_int, [C.POINTER(_vp), _u64p, C.c_int32, _u8p, C.c_int32, C.c_int32]),
     "mgwfbp_ctx_create_host": (C.c_int, [C.POINTER(_vp), _u64p, C.c_int32, _u8p, C.c_int32, C.c_int32]),
     "mgwfbp_ctx_destroy": (None, [_vp]),
@@ -64,6 +63,8 @@ _SIGNATURES = {
     "mgwfbp_group_pipeline": (C.c_int, [_vp, C.c_int32, _vp, _vp, _vp, _vp, _vp, C.c_float, C.c_float, _vp]),
     "mgwfbp_direct_update": (C.c_int, [_vp, C.c_int32, _vp, _vp, _vp, _vp, C.c_float, C.c_float, _vp]),
     "mgwfbp_group_pipeline_span": (C.c_int, [_vp, C.c_int32, C.c_int32, _vp, _vp, _vp, _vp, _vp, C.c_float, C.c_float, _vp]),
+    "mgwfbp_handler_replay": (C.c_int, [_vp, _f64p, C.c_double, C.POINTER(_vp), C.c_int32, _vp, _vp, _vp, _vp, _vp,
+                                        C.c_float, C.c_float, _f64p]),
     "mgwfbp_last_hip_error": (C.c_int, []),
     "mgwfbp_version": (C.c_char_p, []),
 }
@@ -148,6 +149,20 @@ def eval_plan(merged: Sequence[int], size_bytes: Sequence[int], t_backward_s: Se
     return out.value
 
 
+def group_ready_times(merged: Sequence[int], t_backward_s: Sequence[float]) -> np.ndarray:
+    """mgwfbp_group_ready_times -> ready[G], seconds from the start of the backward pass."""
+    m = _arr(merged, np.uint8)
+    tb = _arr(t_backward_s, np.float64)
+    if m.shape[0] != tb.shape[0]:
+        raise ValueError("merged and t_backward_s differ in length")
+    L = int(m.shape[0])
+    out = np.zeros(max(L, 1), np.float64)
+    G = C.c_int32(0)
+    _check("mgwfbp_group_ready_times", lib().mgwfbp_group_ready_times(_ptr(m, _u8p), _ptr(tb, _f64p), L,
+                                                                      _ptr(out, _f64p), C.byref(G)))
+    return out[:G.value].copy()
+
+
 AR_BINARY_TREE, AR_RECURSIVE_DOUBLING, AR_HALVING_DOUBLING, AR_DOUBLE_BINARY_TREES, AR_RING = range(5)
 
 
@@ -186,16 +201,6 @@ def simulate(size_bytes: Sequence[int], t_backward_s: Sequence[float], t_forward
         float(beta_s_per_byte), float(gamma_s_per_byte), _ptr(wc, _i32p), n, _ptr(tw, _f64p), _ptr(ts, _f64p),
         _ptr(tm, _f64p), _ptr(g, _i32p)))
     return tw, ts, tm, g
-
-
-def stream_probe(read_ptrs: Sequence[int], write_ptrs: Sequence[int], update_ptrs: Sequence[int], elems: int,
-                 stream: int = 0) -> None:
-    """mgwfbp_stream_probe: the arguments are lists of device addresses of binary32 arrays of `elems` elements."""
-    def table(addrs):
-        return (_vp * max(len(addrs), 1))(*[int(a) for a in addrs]) if addrs else None
-    r, w, x = table(read_ptrs), table(write_ptrs), table(update_ptrs)
-    _check("mgwfbp_stream_probe", lib().mgwfbp_stream_probe(r, len(read_ptrs), w, len(write_ptrs), x, len(update_ptrs),
-                                                          int(elems), _vp(stream)))
 
 
 # --------------------------------------------------------------------------------------------
@@ -312,3 +317,17 @@ class Context:
         _check("mgwfbp_group_pipeline_span", lib().mgwfbp_group_pipeline_span(
             self._h, int(group_first), int(group_count), _vp(d_grad_ptrs), _vp(d_merge_bufs), _vp(d_reduced or None),
             _vp(d_w_ptrs), _vp(d_v_ptrs), float(lr), float(momentum), _vp(stream)))
+
+    def handler_replay(self, group_ready_s: Sequence[float], time_scale: float, streams: Sequence[int],
+                       d_grad_ptrs: int, d_merge_bufs: int, d_reduced: int, d_w_ptrs: int, d_v_ptrs: int,
+                       lr: float, momentum: float):
+        """mgwfbp_handler_replay (blocks until the work is done) -> (launches, last_ready_s, done_s, exposed_s)."""
+        ready = _arr(group_ready_s, np.float64)
+        if ready.shape[0] != self.n_groups:
+            raise ValueError("group_ready_s must have one entry per group")
+        table = (_vp * max(len(streams), 1))(*[int(x) for x in streams])
+        stats = np.zeros(4, np.float64)
+        _check("mgwfbp_handler_replay", lib().mgwfbp_handler_replay(
+            self._h, _ptr(ready, _f64p), float(time_scale), table, len(streams), _vp(d_grad_ptrs), _vp(d_merge_bufs),
+            _vp(d_reduced or None), _vp(d_w_ptrs), _vp(d_v_ptrs), float(lr), float(momentum), _ptr(stats, _f64p)))
+        return int(stats[0]), float(stats[1]), float(stats[2]), float(stats[3])

@@ -1,4 +1,5 @@
-"""Compiles the HIP/C++ sources under csrc/ into libmgwfbp.so next to this file (gfx950 only)."""
+"""Compiles the HIP/C++ sources under csrc/ into libmgwfbp.so next to this file, and the benchmark's
+measurement aid under bench_aid/ into its own shared object there (gfx950 only)."""
 from __future__ import annotations
 
 import os
@@ -10,7 +11,9 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB_NAME = "libmgwfbp.so"
-SOURCES = ("plan.cpp", "model.cpp", "layout.cpp", "kernels.hip", "probe.hip")
+SOURCES = ("plan.cpp", "model.cpp", "layout.cpp", "kernels.hip")
+AID_DIR = os.path.join(ROOT, "bench_aid")
+AID_LIB = os.path.join(AID_DIR, "libmgwfbp_bench_aid.so")
 
 # -ffp-contract=off: the update and the reduction promise one rounding per operation.
 # The packed-fp32 feature is switched off for device code: packed single-precision instructions are
@@ -45,5 +48,18 @@ def build_library(out: Optional[str] = None, defines: Optional[Dict[str, object]
     return out
 
 
+def build_bench_aid(verbose: bool = False) -> str:
+    """The stream probe and cache scrub that bench.py uses; kept out of libmgwfbp.so on purpose."""
+    hipcc = shutil.which("hipcc") or "/opt/rocm/bin/hipcc"
+    cmd = [hipcc] + HIPCC_FLAGS + ["-I", AID_DIR, "-x", "hip", os.path.join(AID_DIR, "stream_probe.hip"), "-o", AID_LIB]
+    if verbose:
+        print(" ".join(cmd), flush=True)
+    res = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
+    if res.returncode != 0:
+        raise RuntimeError(f"hipcc failed ({res.returncode}):\n{res.stdout}")
+    return AID_LIB
+
+
 if __name__ == "__main__":  # python -m paper_1912_09268_amd.build
     print(build_library(verbose=True))
+    print(build_bench_aid(verbose=True))

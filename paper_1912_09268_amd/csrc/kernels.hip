@@ -40,8 +40,12 @@
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
+#include <atomic>
+#include <chrono>
+#include <cmath>
 #include <cstdint>
 #include <cstring>
+#include <mutex>
 #include <new>
 
 #include "mgwfbp.h"
@@ -300,9 +304,121 @@ __device__ __forceinline__ void do_one(const Args<GradT>& A, const WorkerPtrs<Gr
 // ---------------------------------------------------------------------------------------------
 // fast path: the whole tile belongs to one tensor
 // ---------------------------------------------------------------------------------------------
-template <int KIND, typename GradT, int PT, bool WVNT>
-__device__ __forceinline__ void fast_tile(const Args<GradT>& A, const WorkerPtrs<GradT, PT>& mrg,
-                                          int layer, int64_t tensor_off, int64_t tile_base) {
+// Order of the memory instructions of a fast tile:
+//   all loads first   every load of the chunk (P gradient vectors + w + v per vector) before its first store;
+//   worker by worker  load one worker's share of the chunk, store it into that worker's merge arena, add it to
+//                     the running sums, go on to the next worker; w and v come last.  At any moment a workgroup
+//                     then reads one array and writes one array, U * 4 KiB (binary32) of each at a stretch, and
+//                     a lane holds the running sums and one worker's share instead of all P.
+// Measured with the memory-side cache emptied before every launch: worker by worker is 1-3 % faster for binary32
+// gradients; for 16-bit gradients, whose shares are half as long, all loads first is 1-2 % faster up to 4 vectors
+// per lane and would need more than 200 registers beyond that.
+template <typename GradT, int U> constexpr bool worker_by_worker() { return sizeof(GradT) == 4 || U >= 8; }
+
+// All loads first.
+template <int KIND, typename GradT, int PT, bool WVNT, int U>
+__device__ __forceinline__ void fast_chunk_all_loads_first(const Args<GradT>& A, const WorkerPtrs<const GradT, PT>& src,
+                                                           const WorkerPtrs<GradT, PT>& mrg, float* wp, float* vp,
+                                                           int64_t tensor_off, int64_t tile_base) {
+    Regs<GradT, PT, VEC> R[U];
+    const int lane_elem = static_cast<int>(threadIdx.x) * VEC;
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        const int p = u * (BLOCK * VEC) + lane_elem;
+        load_phase<KIND, GradT, PT, VEC, WVNT>(R[u], A, src, mrg, wp, vp, tensor_off + p, tile_base + p);
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        const int p = u * (BLOCK * VEC) + lane_elem;
+        store_phase<KIND, GradT, PT, VEC, WVNT>(R[u], A, src, mrg, wp, vp, tensor_off + p, tile_base + p);
+    }
+}
+
+// Worker by worker.  The sums are taken in worker order, acc = g_0, then acc = acc + g_w, exactly as in
+// store_phase, so both orders give the same bits.
+template <int KIND, typename GradT, int PT, bool WVNT, int U>
+__device__ __forceinline__ void fast_chunk_worker_by_worker(const Args<GradT>& A, const WorkerPtrs<const GradT, PT>& src,
+                                                            const WorkerPtrs<GradT, PT>& mrg, float* wp, float* vp,
+                                                            int64_t tensor_off, int64_t tile_base) {
+    typedef typename VecOf<GradT, VEC>::type GV;
+    constexpr int STEP = BLOCK * VEC;
+    const int lane_elem = static_cast<int>(threadIdx.x) * VEC;
+    const int64_t soff = tensor_off + lane_elem;    // this lane's first element: in its tensor
+    const int64_t apos = tile_base + lane_elem;     //                            in the arena
+    f32x4 acc[U];
+    if constexpr (reads_grads(KIND) || reads_merge(KIND)) {
+        auto one_worker = [&](int w) {
+            const GradT* from;
+            if constexpr (reads_grads(KIND)) from = src.get(w) + soff;
+            else from = mrg.get(w) + apos;
+            GV g[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u) g[u] = ld<NT_LD, GV>(from + u * STEP);
+            if constexpr (writes_merge(KIND)) {
+                GradT* to = mrg.get(w) + apos;
+#pragma unroll
+                for (int u = 0; u < U; ++u) st<NT_ST, GV>(to + u * STEP, g[u]);
+            }
+            if constexpr (sums(KIND)) {
+#pragma unroll
+                for (int u = 0; u < U; ++u)
+#pragma unroll
+                    for (int c = 0; c < VEC; ++c) {
+                        const float x = widen(g[u][c]);
+                        acc[u][c] = (w == 0) ? x : acc[u][c] + x;
+                    }
+            }
+        };
+        if constexpr (PT > 0) {
+#pragma unroll
+            for (int w = 0; w < PT; ++w) one_worker(w);
+        } else {
+            for (int w = 0; w < A.P; ++w) one_worker(w);
+        }
+        if constexpr (sums(KIND)) {
+#pragma unroll
+            for (int u = 0; u < U; ++u)
+#pragma unroll
+                for (int c = 0; c < VEC; ++c) acc[u][c] = acc[u][c] * A.inv_p;
+        }
+    }
+    if constexpr (KIND == K_UPDATE) {
+#pragma unroll
+        for (int u = 0; u < U; ++u) acc[u] = ld<NT_LD, f32x4>(A.reduced + apos + u * STEP);
+    }
+    if constexpr (writes_reduced(KIND)) {
+        if (KIND == K_REDUCE || A.reduced != nullptr) {
+#pragma unroll
+            for (int u = 0; u < U; ++u) st<NT_ST, f32x4>(A.reduced + apos + u * STEP, acc[u]);
+        }
+    }
+    if constexpr (updates(KIND)) {
+        f32x4 v[U], w[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) v[u] = ld<WVNT, f32x4>(vp + soff + u * STEP);
+#pragma unroll
+        for (int u = 0; u < U; ++u) w[u] = ld<WVNT, f32x4>(wp + soff + u * STEP);
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+#pragma unroll
+            for (int c = 0; c < VEC; ++c) {
+                const float t1 = A.mu * v[u][c];
+                const float v1 = t1 + acc[u][c];
+                const float t2 = A.lr * v1;
+                v[u][c] = v1;
+                w[u][c] = w[u][c] - t2;
+            }
+            st<WVNT, f32x4>(vp + soff + u * STEP, v[u]);
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) st<WVNT, f32x4>(wp + soff + u * STEP, w[u]);
+    }
+}
+
+// RUN consecutive tiles that lie inside the same tensor, handled as one chunk of RUN * TVECS vectors per lane.
+template <int KIND, typename GradT, int PT, bool WVNT, int RUN>
+__device__ __forceinline__ void fast_tiles(const Args<GradT>& A, const WorkerPtrs<GradT, PT>& mrg,
+                                           int layer, int64_t tensor_off, int64_t tile_base) {
     WorkerPtrs<const GradT, PT> src;
     float* wp = nullptr;
     float* vp = nullptr;
@@ -311,18 +427,28 @@ __device__ __forceinline__ void fast_tile(const Args<GradT>& A, const WorkerPtrs
         wp = ro(A.w_ptrs)[layer];
         vp = ro(A.v_ptrs)[layer];
     }
-    Regs<GradT, PT, VEC> R[TVECS];
-    const int lane_elem = static_cast<int>(threadIdx.x) * VEC;
-#pragma unroll
-    for (int u = 0; u < TVECS; ++u) {
-        const int p = u * (BLOCK * VEC) + lane_elem;
-        load_phase<KIND, GradT, PT, VEC, WVNT>(R[u], A, src, mrg, wp, vp, tensor_off + p, tile_base + p);
+    if constexpr (worker_by_worker<GradT, RUN * TVECS>() || KIND == K_UPDATE)
+        fast_chunk_worker_by_worker<KIND, GradT, PT, WVNT, RUN * TVECS>(A, src, mrg, wp, vp, tensor_off, tile_base);
+    else
+        fast_chunk_all_loads_first<KIND, GradT, PT, WVNT, RUN * TVECS>(A, src, mrg, wp, vp, tensor_off, tile_base);
+}
+
+template <int KIND, typename GradT, int PT, bool WVNT, int MAXRUN>
+__device__ __forceinline__ void fast_run(int run, const Args<GradT>& A, const WorkerPtrs<GradT, PT>& mrg,
+                                         int layer, int64_t tensor_off, int64_t tile_base) {
+    if constexpr (MAXRUN >= 4) {
+        if (run == 4) {
+            fast_tiles<KIND, GradT, PT, WVNT, 4>(A, mrg, layer, tensor_off, tile_base);
+            return;
+        }
     }
-#pragma unroll
-    for (int u = 0; u < TVECS; ++u) {
-        const int p = u * (BLOCK * VEC) + lane_elem;
-        store_phase<KIND, GradT, PT, VEC, WVNT>(R[u], A, src, mrg, wp, vp, tensor_off + p, tile_base + p);
+    if constexpr (MAXRUN >= 2) {
+        if (run == 2) {
+            fast_tiles<KIND, GradT, PT, WVNT, 2>(A, mrg, layer, tensor_off, tile_base);
+            return;
+        }
     }
+    fast_tiles<KIND, GradT, PT, WVNT, 1>(A, mrg, layer, tensor_off, tile_base);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -435,7 +561,10 @@ __device__ __forceinline__ TileHdr load_header(const TileHdr* p) {
     return h;
 }
 
-template <int KIND, typename GradT, int PT>
+// MAXRUN (1, 2 or 4): how many consecutive full tiles of one tensor a workgroup may take together as one chunk.
+// It is a template parameter because the registers a kernel is given are those of its hungriest path: a
+// launch that never fuses tiles should not pay (in waves per SIMD) for the long-chunk path.
+template <int KIND, typename GradT, int PT, int MAXRUN>
 __global__ void __launch_bounds__(MGWFBP_BLOCK) mgwfbp_stream_kernel(const Args<GradT> A) {
     __shared__ int s_loc[MAXSEG + 1];
     __shared__ int s_layer[MAXSEG];
@@ -461,34 +590,57 @@ __global__ void __launch_bounds__(MGWFBP_BLOCK) mgwfbp_stream_kernel(const Args<
         u_end = n_units;
         u_step = gridDim.x;
     }
-    for (int u = u_begin; u < u_end; u += u_step)
-    for (int t = u * K; t < min((u + 1) * K, A.tile_count); ++t) {
-        const int tile = A.tile_first + t;
-        const TileHdr h = load_header(A.tiles + tile);
-        const int64_t tile_base = static_cast<int64_t>(tile) * TILE;
-        int clo = 0, chi = h.valid;
-        if (A.clipped) {                        // uniform over the workgroup
-            const int64_t l = A.clip_lo - tile_base, u = A.clip_hi - tile_base;
-            if (l > 0) clo = l < h.valid ? static_cast<int>(l) : h.valid;
-            if (u < h.valid) chi = u > 0 ? static_cast<int>(u) : 0;
-            if (chi <= clo) continue;
-        }
-        if (clo == 0 && chi == TILE && (!needs_owner(KIND) || h.nseg == 1)) {
+    for (int u = u_begin; u < u_end; u += u_step) {
+        const int t_end = min((u + 1) * K, A.tile_count);
+        int t = u * K;
+        while (t < t_end) {
+            const int tile = A.tile_first + t;
+            const TileHdr h = load_header(A.tiles + tile);
+            const int64_t tile_base = static_cast<int64_t>(tile) * TILE;
+            int clo = 0, chi = h.valid;
+            if (A.clipped) {                        // uniform over the workgroup
+                const int64_t l = A.clip_lo - tile_base, r = A.clip_hi - tile_base;
+                if (l > 0) clo = l < h.valid ? static_cast<int>(l) : h.valid;
+                if (r < h.valid) chi = r > 0 ? static_cast<int>(r) : 0;
+                if (chi <= clo) {
+                    ++t;
+                    continue;
+                }
+            }
+            if (!(clo == 0 && chi == TILE && (!needs_owner(KIND) || h.nseg == 1))) {
+                general_tile<KIND, GradT, PT>(A, mrg, h, tile_base, clo, chi, s_loc, s_layer, s_wave);
+                ++t;
+                continue;
+            }
+            // A full tile inside one tensor.  If the workgroup has more tiles to do and the next one (or the
+            // next three) are full tiles of the same tensor with the same cache policy, they are taken
+            // together as one longer chunk (same work per element, longer stretches per array).
+            int run = 1;
+            if (MAXRUN > 1 && !A.clipped && t + 1 < t_end) {
+                const int left = t_end - t;
+                const TileHdr h1 = load_header(A.tiles + tile + 1);
+                const TileHdr h2 = load_header(A.tiles + tile + (left > 2 ? 2 : 1));
+                const TileHdr h3 = load_header(A.tiles + tile + (left > 3 ? 3 : 1));
+                auto joins = [&](const TileHdr& x) {
+                    return x.valid == TILE && x.flags == h.flags && (!needs_owner(KIND) || (x.nseg == 1 && x.layer0 == h.layer0));
+                };
+                if (joins(h1)) run = (MAXRUN >= 4 && left >= 4 && joins(h2) && joins(h3)) ? 4 : 2;
+            }
             // Tiles flagged "resident" keep their w and v in the memory-side cache between iterations
             // (ordinary loads and stores); all other w, v traffic is streamed past it like the gradients.
             // The two arms differ only in the cache policy of their memory instructions; the empty asm
             // statements keep the optimiser from merging them back into one (which drops the policy).
+            const int64_t toff = -h.first_start;
             if (!updates(KIND) || (h.flags & 1)) {
                 asm volatile("; w and v cacheable" ::: "memory");
-                fast_tile<KIND, GradT, PT, NT_WV>(A, mrg, h.layer0, -h.first_start, tile_base);
+                fast_run<KIND, GradT, PT, NT_WV, MAXRUN>(run, A, mrg, h.layer0, toff, tile_base);
                 asm volatile("; end w and v cacheable" ::: "memory");
             } else {
                 asm volatile("; w and v streamed" ::: "memory");
-                fast_tile<KIND, GradT, PT, true>(A, mrg, h.layer0, -h.first_start, tile_base);
+                fast_run<KIND, GradT, PT, true, MAXRUN>(run, A, mrg, h.layer0, toff, tile_base);
                 asm volatile("; end w and v streamed" ::: "memory");
             }
-        } else {
-            general_tile<KIND, GradT, PT>(A, mrg, h, tile_base, clo, chi, s_loc, s_layer, s_wave);
+            t += run;
         }
     }
 }
@@ -519,6 +671,7 @@ struct mgwfbp_ctx {
     int32_t xcd_contiguous = 0;
     int32_t tiles_per_wg = 0;         // 0 = per-kernel default
     uint64_t resident_bytes = 0;      // budget of w + v bytes kept cacheable
+    uint64_t serial = 0;              // changes whenever the tables change; never reused within a process
     // device copies
     TileHdr* d_tiles = nullptr;
     uint32_t* d_seg_n = nullptr;
@@ -533,8 +686,11 @@ namespace {
 // persistent grid for every profile.
 constexpr int32_t DEFAULT_BLOCKS_PER_CU = 0;
 
-// Default share of the 256 MB memory-side cache given to weights and momenta.
-constexpr uint64_t DEFAULT_RESIDENT_BYTES = 232ull << 20;
+// Default share of the 256 MB memory-side cache given to weights and momenta: none.  In a training loop a
+// forward and a backward pass run between two updates, so nothing of one update is still cached at the next.
+constexpr uint64_t DEFAULT_RESIDENT_BYTES = 0;
+
+std::atomic<uint64_t> g_next_serial{1};
 
 // Marks the leading tiles whose w + v bytes (8 per element) fit into the budget.
 void mark_resident_tiles(HostTables& h, uint64_t budget) {
@@ -579,6 +735,7 @@ int create_common(mgwfbp_ctx** out, const uint64_t* n_elems, int32_t L, const ui
     c->dtype = dtype;
     c->blocks_per_cu = DEFAULT_BLOCKS_PER_CU;
     c->resident_bytes = DEFAULT_RESIDENT_BYTES;
+    c->serial = g_next_serial.fetch_add(1);
     mark_resident_tiles(c->host, c->resident_bytes);
     if (device) {
         hipDeviceProp_t prop;
@@ -603,7 +760,13 @@ int create_common(mgwfbp_ctx** out, const uint64_t* n_elems, int32_t L, const ui
 
 template <int KIND, typename GradT, int PT>
 int launch_one(const Args<GradT>& A, int grid, hipStream_t stream, int grid_y = 1) {
-    hipLaunchKernelGGL((mgwfbp_stream_kernel<KIND, GradT, PT>), dim3(grid, grid_y), dim3(BLOCK), 0, stream, A);
+    // the longest run of tiles a workgroup could fuse is bounded by the tiles it is given
+    if (A.tiles_per_wg >= 4 && !A.clipped)
+        hipLaunchKernelGGL((mgwfbp_stream_kernel<KIND, GradT, PT, 4>), dim3(grid, grid_y), dim3(BLOCK), 0, stream, A);
+    else if (A.tiles_per_wg >= 2 && !A.clipped)
+        hipLaunchKernelGGL((mgwfbp_stream_kernel<KIND, GradT, PT, 2>), dim3(grid, grid_y), dim3(BLOCK), 0, stream, A);
+    else
+        hipLaunchKernelGGL((mgwfbp_stream_kernel<KIND, GradT, PT, 1>), dim3(grid, grid_y), dim3(BLOCK), 0, stream, A);
     return note(hipGetLastError());
 }
 
@@ -626,6 +789,14 @@ int launch_by_p(const Args<GradT>& A, int grid, hipStream_t stream) {
     }
 }
 
+// Where the kernels find the tables: normally the context's own device copies.
+struct DevTables {
+    const TileHdr* tiles;
+    const uint32_t* seg_n;
+    const int32_t* seg_layer;
+    const uint64_t* seg_off;
+};
+
 // Tile range and element clip of one call: either a group (or all groups), or an arena interval.
 struct Span {
     int32_t t0 = 0, t1 = 0;
@@ -636,8 +807,8 @@ struct Span {
 template <int KIND>
 int run(mgwfbp_ctx* c, int32_t group, const void* const* grad_ptrs, void* const* merge_bufs, float* reduced,
         float* const* w_ptrs, float* const* v_ptrs, float lr, float mu, void* stream_v,
-        const Span* span = nullptr) {
-    if (c == nullptr || !c->on_device) return MGWFBP_EINVAL;
+        const Span* span = nullptr, const DevTables* tabs = nullptr) {
+    if (c == nullptr || (tabs == nullptr && !c->on_device)) return MGWFBP_EINVAL;
     if (span == nullptr && (group < -1 || group >= c->host.G)) return MGWFBP_EINVAL;
     if (reads_grads(KIND) && grad_ptrs == nullptr) return MGWFBP_EINVAL;
     if ((reads_merge(KIND) || writes_merge(KIND)) && merge_bufs == nullptr) return MGWFBP_EINVAL;
@@ -658,10 +829,15 @@ int run(mgwfbp_ctx* c, int32_t group, const void* const* grad_ptrs, void* const*
     const int32_t count = t1 - t0;
     if (count <= 0) return MGWFBP_OK;             // nothing to move (empty group or empty model)
 
-    int dev = -1;
-    int rc = note(hipGetDevice(&dev));
-    if (rc != MGWFBP_OK) return rc;
-    if (dev != c->device) return MGWFBP_EINVAL;   // tables live on the device the context was made on
+    DevTables T{c->d_tiles, c->d_seg_n, c->d_seg_layer, c->d_seg_off};
+    if (tabs != nullptr) {
+        T = *tabs;                                    // the caller vouches for the current device
+    } else {
+        int dev = -1;
+        int rc = note(hipGetDevice(&dev));
+        if (rc != MGWFBP_OK) return rc;
+        if (dev != c->device) return MGWFBP_EINVAL;   // tables live on the device the context was made on
+    }
 
     // tiles per workgroup: PACK runs as single-worker copies, whose tiles are small (one stream in, one
     // out), so it takes several tiles per workgroup to keep the dispatcher from being the limit
@@ -669,7 +845,7 @@ int run(mgwfbp_ctx* c, int32_t group, const void* const* grad_ptrs, void* const*
     if (tpw <= 0) tpw = (KIND == K_PACK) ? std::max(1, 16384 / (TILE * (c->dtype == MGWFBP_F32 ? 4 : 2))) : 1;
     const int32_t units = (count + tpw - 1) / tpw;
     int grid = units;
-    if (c->blocks_per_cu > 0 && static_cast<int64_t>(c->n_cu) * c->blocks_per_cu < units)
+    if (c->blocks_per_cu > 0 && c->n_cu > 0 && static_cast<int64_t>(c->n_cu) * c->blocks_per_cu < units)
         grid = c->n_cu * c->blocks_per_cu;
     int32_t xcd = 0;
     if (c->xcd_contiguous && grid >= 64) {
@@ -682,14 +858,14 @@ int run(mgwfbp_ctx* c, int32_t group, const void* const* grad_ptrs, void* const*
     const int64_t clip_lo = span ? span->lo : 0, clip_hi = span ? span->hi : 0;
 
     if (c->dtype == MGWFBP_F32) {
-        Args<float> A{c->d_tiles, c->d_seg_n, c->d_seg_layer, c->d_seg_off,
+        Args<float> A{T.tiles, T.seg_n, T.seg_layer, T.seg_off,
                       reinterpret_cast<const float* const*>(grad_ptrs),
                       reinterpret_cast<float* const*>(merge_bufs), reduced, w_ptrs, v_ptrs,
                       lr, mu, inv_p, c->host.L, c->P, t0, count, xcd, tpw, units, 0,
                       clip_on, clip_lo, clip_hi};
         return launch_by_p<KIND, float>(A, grid, stream);
     }
-    Args<uint16_t> A{c->d_tiles, c->d_seg_n, c->d_seg_layer, c->d_seg_off,
+    Args<uint16_t> A{T.tiles, T.seg_n, T.seg_layer, T.seg_off,
                      reinterpret_cast<const uint16_t* const*>(grad_ptrs),
                      reinterpret_cast<uint16_t* const*>(merge_bufs), reduced, w_ptrs, v_ptrs,
                      lr, mu, inv_p, c->host.L, c->P, t0, count, xcd, tpw, units, 0,
@@ -769,6 +945,7 @@ int mgwfbp_ctx_set_launch(mgwfbp_ctx* c, int32_t blocks_per_cu, int32_t xcd_cont
 int mgwfbp_ctx_set_resident_bytes(mgwfbp_ctx* c, uint64_t bytes) {
     if (c == nullptr) return MGWFBP_EINVAL;
     c->resident_bytes = bytes;
+    c->serial = g_next_serial.fetch_add(1);
     mark_resident_tiles(c->host, bytes);
     if (c->on_device && !c->host.tiles.empty())
         return note(hipMemcpy(c->d_tiles, c->host.tiles.data(), c->host.tiles.size() * sizeof(TileHdr),
@@ -842,6 +1019,52 @@ int mgwfbp_group_pipeline_span(mgwfbp_ctx* c, int32_t group_first, int32_t group
     s.t1 = c->host.group_tile[static_cast<size_t>(group_first + group_count)];
     return run<K_PIPELINE>(c, 0, d_grad_ptrs, d_merge_bufs, d_reduced, d_w_ptrs, d_v_ptrs, lr, momentum,
                            hip_stream, &s);
+}
+
+int mgwfbp_handler_replay(mgwfbp_ctx* c, const double* group_ready_s, double time_scale, void* const* streams,
+                          int32_t n_streams, const void* const* d_grad_ptrs, void* const* d_merge_bufs,
+                          float* d_reduced, float* const* d_w_ptrs, float* const* d_v_ptrs, float lr, float momentum,
+                          double* stats_out) {
+    if (c == nullptr || !c->on_device || streams == nullptr || n_streams < 1 || n_streams > 16) return MGWFBP_EINVAL;
+    if (!std::isfinite(time_scale) || time_scale < 0.0) return MGWFBP_EINVAL;
+    const int32_t G = c->host.G;
+    if (G > 0 && group_ready_s == nullptr) return MGWFBP_EINVAL;
+    for (int32_t k = 0; k < G; ++k) {
+        if (!std::isfinite(group_ready_s[k]) || group_ready_s[k] < 0.0) return MGWFBP_EINVAL;
+        if (k > 0 && group_ready_s[k] < group_ready_s[k - 1]) return MGWFBP_EINVAL;
+    }
+    typedef std::chrono::steady_clock Clock;
+    const Clock::time_point t0 = Clock::now();
+    auto since_t0 = [&]() { return std::chrono::duration<double>(Clock::now() - t0).count(); };
+    int32_t next = 0, launches = 0;
+    int rc = MGWFBP_OK;
+    while (next < G && rc == MGWFBP_OK) {
+        const double due = time_scale * group_ready_s[next];
+        double now = since_t0();
+        while (now < due) now = since_t0();       // the backward pass has not produced this group yet
+        int32_t upto = next + 1;                  // everything that filled meanwhile goes into the same launch
+        while (upto < G && time_scale * group_ready_s[upto] <= now) ++upto;
+        Span s;
+        s.t0 = c->host.group_tile[static_cast<size_t>(next)];
+        s.t1 = c->host.group_tile[static_cast<size_t>(upto)];
+        rc = run<K_PIPELINE>(c, 0, d_grad_ptrs, d_merge_bufs, d_reduced, d_w_ptrs, d_v_ptrs, lr, momentum,
+                             streams[launches % n_streams], &s);
+        ++launches;
+        next = upto;
+    }
+    for (int32_t j = 0; j < n_streams; ++j) {     // drain every stream, also after a failed launch
+        const int rj = note(hipStreamSynchronize(static_cast<hipStream_t>(streams[j])));
+        if (rc == MGWFBP_OK) rc = rj;
+    }
+    const double done = since_t0();
+    if (stats_out != nullptr) {
+        const double last = G > 0 ? time_scale * group_ready_s[G - 1] : 0.0;
+        stats_out[0] = static_cast<double>(launches);
+        stats_out[1] = last;
+        stats_out[2] = done;
+        stats_out[3] = done - last;
+    }
+    return rc;
 }
 
 int mgwfbp_direct_update(mgwfbp_ctx* c, int32_t group, const void* const* d_grad_ptrs, float* d_reduced,

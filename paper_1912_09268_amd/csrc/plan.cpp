@@ -93,6 +93,25 @@ extern "C" int mgwfbp_plan(const uint64_t* size_bytes, const double* t_backward_
     return MGWFBP_OK;
 }
 
+// Eq. 6: group k's merge buffer is full when the gradient of its lowest layer exists.
+extern "C" int mgwfbp_group_ready_times(const uint8_t* merged, const double* t_backward_s, int32_t L,
+                                        double* ready_out, int32_t* n_groups_out) {
+    if (L < 0 || (L > 0 && (merged == nullptr || t_backward_s == nullptr || merged[0] != 0))) return MGWFBP_EINVAL;
+    for (int32_t i = 0; i < L; ++i)
+        if (merged[i] > 1 || !valid_time(t_backward_s[i])) return MGWFBP_EINVAL;
+    std::vector<double> ready;
+    gradient_ready_times(t_backward_s, L, ready);
+    int32_t G = 0;
+    for (int32_t i = L - 1; i >= 0; --i) {
+        if (merged[i] == 0) {                      // a normal layer closes the group it arrives in
+            if (ready_out) ready_out[G] = ready[static_cast<size_t>(i)];
+            ++G;
+        }
+    }
+    if (n_groups_out) *n_groups_out = G;
+    return MGWFBP_OK;
+}
+
 extern "C" int mgwfbp_eval(const uint8_t* merged, const uint64_t* size_bytes,
                            const double* t_backward_s, int32_t L, double a, double b,
                            double* t_iter_out) {

@@ -166,3 +166,10 @@ class DeviceModel:
         self.ctx.group_pipeline_span(group_first, group_count, self.grad_ptrs.data_ptr(), self.merge_ptrs.data_ptr(),
                                      self.reduced.data_ptr() if write_reduced else 0,
                                      self.w_ptrs.data_ptr(), self.v_ptrs.data_ptr(), lr, momentum, self._stream())
+
+    def handler_replay(self, lr: float, momentum: float, group_ready_s, time_scale: float, streams,
+                       write_reduced: bool = False):
+        """Blocks until done; `streams` are raw stream handles.  Returns the library's four statistics."""
+        return self.ctx.handler_replay(group_ready_s, time_scale, streams, self.grad_ptrs.data_ptr(),
+                                       self.merge_ptrs.data_ptr(), self.reduced.data_ptr() if write_reduced else 0,
+                                       self.w_ptrs.data_ptr(), self.v_ptrs.data_ptr(), lr, momentum)

@@ -13,7 +13,8 @@ from oracle import plan as OP
 pytestmark = pytest.mark.gpu
 
 MODES = ("staged", "staged_per_group", "reduce_update", "pipeline", "pipeline_per_group", "pipeline_no_reduced",
-         "pipeline_spans", "direct", "direct_per_group_with_reduced", "pipeline_two_streams")
+         "pipeline_spans", "direct", "direct_per_group_with_reduced", "pipeline_two_streams",
+         "handler_replay_at_once", "handler_replay_on_a_schedule")
 NO_REDUCED = ("reduce_update", "pipeline_no_reduced", "direct")
 NO_MERGE = ("direct", "direct_per_group_with_reduced")
 
@@ -63,6 +64,22 @@ def _run_mode(dm, mode, lr, mu, G):
                 dm.group_pipeline(lr, mu, k)
         for s in side:
             main.wait_stream(s)
+    elif mode == "handler_replay_at_once":        # every group full at t0: one launch on the current stream
+        import torch
+        stats = dm.handler_replay(lr, mu, np.linspace(0.0, 1e-3, G), 0.0,
+                                  [int(torch.cuda.current_stream().cuda_stream)], write_reduced=True)
+        assert stats[0] == (1 if G else 0) and stats[1] == 0.0 and stats[3] == stats[2] >= 0.0
+    elif mode == "handler_replay_on_a_schedule":  # a group every 40 us on three streams: several launches
+        import torch
+        main = torch.cuda.current_stream()
+        side = [torch.cuda.Stream() for _ in range(3)]          # default priority
+        for s in side:
+            s.wait_stream(main)
+        ready = 40e-6 * np.arange(G)
+        stats = dm.handler_replay(lr, mu, ready, 1.0, [int(s.cuda_stream) for s in side], write_reduced=True)
+        assert 1 <= stats[0] <= G or G == 0
+        assert stats[1] == (ready[-1] if G else 0.0) and stats[2] >= stats[1]
+        _say(f"[parity]   handler replay: {stats[0]} launches for {G} groups, exposed {1e6 * stats[3]:.0f} us")
     elif mode == "direct":                        # merge arenas never written
         dm.direct_update(lr, mu)
     elif mode == "direct_per_group_with_reduced":
@@ -287,6 +304,16 @@ def test_device_entry_points_reject_bad_arguments():
         dm.group_pipeline_span(0.1, 0.9, 1, 1)       # the model has one group only
     with pytest.raises(M.MgwfbpError):
         dm.group_pipeline_span(0.1, 0.9, -1, 1)
+    ctx.close()
+    # the handler replay checks its schedule and its streams before it launches anything
+    ctx = M.Context([100, 100, 100], [0, 0, 0], 2, M.F32)
+    dm = H.DeviceModel(ctx, [100, 100, 100])
+    for ready, scale, streams in (([0.0, 2e-6, 1e-6], 1.0, [0]), ([0.0, 1e-6, float("nan")], 1.0, [0]),
+                                  ([-1e-6, 0.0, 1e-6], 1.0, [0]), ([0.0, 1e-6, 2e-6], -1.0, [0]),
+                                  ([0.0, 1e-6, 2e-6], float("inf"), [0]), ([0.0, 1e-6, 2e-6], 1.0, []),
+                                  ([0.0, 1e-6, 2e-6], 1.0, [0] * 17)):
+        with pytest.raises(M.MgwfbpError):
+            dm.handler_replay(0.1, 0.9, ready, scale, streams)
     ctx.close()
 
 
@@ -592,42 +619,3 @@ def test_many_random_models(block):
         check_case(p, merged, mode, misalign=int(rng.choice([0, 0, 3, 5])), launch=launch,
                    resident=int(rng.choice([0, 1 << 16, 1 << 30])), seed=int(rng.integers(1, 10 ** 6)),
                    label=f"random block {block} case {case}")
-
-
-# ------------------------------------------------------------------------------------------
-# the measurement aid does what its header says (so that the ceilings bench.py reports mean something)
-# ------------------------------------------------------------------------------------------
-
-@pytest.mark.parametrize("mix", [(1, 0, 0), (8, 0, 0), (0, 1, 0), (1, 1, 0), (2, 4, 1), (8, 8, 2), (8, 0, 2),
-                                 (16, 16, 2), (0, 2, 2), (0, 0, 1)])
-def test_stream_probe_moves_what_it_says(mix):
-    import torch
-    import paper_1912_09268_amd as M
-    r, w, x = mix
-    n = 5 * 2048
-    rng = np.random.default_rng(r * 100 + w * 10 + x)
-    host = [[rng.standard_normal(n).astype(np.float32) for _ in range(c)] for c in mix]
-    dev = [[torch.from_numpy(a).cuda() for a in group] for group in host]
-    _say(f"[probe] mix={mix} n={n}")
-    M.stream_probe(*[[t.data_ptr() for t in group] for group in dev], n, int(torch.cuda.current_stream().cuda_stream))
-    torch.cuda.synchronize()
-    s = np.zeros(n, np.float32)
-    for a in host[0]:
-        s = s + a                                      # binary32, in array order, as the kernel adds
-    for i in range(r):
-        assert np.array_equal(dev[0][i].cpu().numpy(), host[0][i]), "inputs must not change"
-    for i in range(w):
-        want = host[0][i % r] if r else np.ones(n, np.float32)
-        assert np.array_equal(dev[1][i].cpu().numpy(), want)
-    for j in range(x):
-        assert np.array_equal(dev[2][j].cpu().numpy(), host[2][j] + s)
-
-
-def test_stream_probe_rejects_what_it_cannot_run():
-    import torch
-    import paper_1912_09268_amd as M
-    t = torch.zeros(4096, dtype=torch.float32, device="cuda")
-    for args in (([], [], [], 2048), ([t.data_ptr()] * 3, [], [], 2048), ([t.data_ptr()], [], [], 1000),
-                 ([t.data_ptr()], [], [], 0), ([0], [], [], 2048), ([], [], [t.data_ptr()] * 3, 2048)):
-        with pytest.raises(M.MgwfbpError):
-            M.stream_probe(*args)

@@ -147,3 +147,21 @@ def test_plan_opt_hand_example_and_errors():
     assert merged.size == 0 and first.size == 0 and t == 0.0
     with pytest.raises(M.MgwfbpError):
         M.plan_opt([4, 4], [1.0, float("nan")], 1.0, 1.0)
+
+
+def test_group_ready_times_match_the_oracle_bit_for_bit():
+    rng = np.random.default_rng(99)
+    for name in W.PROFILE_NAMES:
+        p = W.make_profile(name)
+        merged, first = M.plan(p.size_bytes, p.t_backward, p.a, p.b)
+        got = M.group_ready_times(merged, p.t_backward)
+        assert got.tolist() == OP.group_ready_times([int(x) for x in merged], [float(x) for x in p.t_backward])
+        assert len(got) == len(first)
+    for _ in range(300):
+        L = int(rng.integers(0, 70))
+        t = rng.uniform(0.0, 1e-3, size=L)
+        m = ([0] + [int(x) for x in rng.integers(0, 2, size=L - 1)]) if L else []
+        assert M.group_ready_times(m, t).tolist() == OP.group_ready_times(m, [float(x) for x in t])
+    for bad in (([1, 0], [1.0, 1.0]), ([0, 2], [1.0, 1.0]), ([0, 0], [1.0, -1.0]), ([0, 0], [1.0, float("nan")])):
+        with pytest.raises(M.MgwfbpError):
+            M.group_ready_times(*bad)

@@ -19,7 +19,8 @@ PLAN_PINS = [TP.test_small_message_example_from_introduction, TP.test_hand_timel
              TP.test_algorithm1_on_hand_example_and_theorem_gap, TP.test_algorithm1_followed_by_hand_on_four_layers,
              TP.test_each_decision_matches_the_layer_type_rule,
              TP.test_limit_large_startup_gives_one_group, TP.test_groups_worked_example,
-             TP.test_group_and_layout_invariants, TP.test_plan_optimal_equals_exhaustive_minimum,
+             TP.test_group_and_layout_invariants, TP.test_group_ready_times_by_hand_and_against_a_running_sum,
+             TP.test_plan_optimal_equals_exhaustive_minimum,
              TP.test_plan_optimal_on_hand_example_and_wide_ranges]
 DATA_PINS = [TD.test_widen_bf16_known_patterns_and_against_torch, TD.test_reduce_bf16_inputs_accumulate_in_binary32,
              TD.test_pack_worked_example, TD.test_pack_round_trip_and_buffer_size, TD.test_reduce_order_is_left_to_right,
@@ -80,6 +81,8 @@ PLAN_MUTANTS = [
     ("groups_in_arrival_order", "for l in range(L, 0, -1):", "for l in range(1, L + 1):"),
     ("groups_in_arrival_order", "if merged[l - 1] == NORMAL:", "if merged[l - 1] == MERGED:"),
     ("merge_layout", "tensor_off[i] = fill", "tensor_off[i] = fill + int(n_elems[i])"),
+    ("group_ready_times", "l = members[-1] + 1", "l = members[0] + 1"),
+    ("group_ready_times", "ready.append(tau_b[l] + t_b1[l])", "ready.append(tau_b[l])"),
 ]
 
 DATA_MUTANTS = [

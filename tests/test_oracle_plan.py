@@ -310,6 +310,34 @@ def test_groups_worked_example():
     assert ge == [150, 30, 30]
 
 
+def test_group_ready_times_by_hand_and_against_a_running_sum():
+    """Pins: (1) the hand timeline of tests/golden/hand_timeline_L3.txt (Eq. 6: gradients of layers 3, 2, 1 exist
+    at 0, 0.9 and 50); (2) with every layer normal the ready times are the running sum of the backward times in
+    arrival order, which numpy.cumsum forms with the same sequence of binary64 additions; (3) any plan's ready
+    times are that sequence picked at the normal layers, and the last one is the whole backward pass."""
+    t_b = [49.1, 0.9, 0.0]
+    assert OP.group_ready_times([0, 0, 0], t_b) == [0.0, 0.9, 50.0]
+    assert OP.group_ready_times([0, 0, 1], t_b) == [0.9, 50.0]          # layers {3,2} then {1}
+    assert OP.group_ready_times([0, 1, 0], t_b) == [0.0, 50.0]          # {3} then {2,1}
+    assert OP.group_ready_times([0, 1, 1], t_b) == [50.0]
+    # the six-layer worked example: groups {6,5,4}, {3}, {2,1} close at layers 4, 3, 1
+    t6 = [1.0, 2.0, 4.0, 8.0, 16.0, 32.0]
+    assert OP.group_ready_times([0, 1, 0, 0, 1, 1], t6) == [32.0 + 16.0 + 8.0, 60.0, 63.0]
+    rng = np.random.default_rng(77)
+    for _ in range(100):
+        L = int(rng.integers(1, 80))
+        t = rng.uniform(0.0, 1e-3, size=L)
+        running = np.cumsum(t[::-1])                                       # arrival order: layer L first
+        assert OP.group_ready_times([0] * L, t) == running.tolist()
+        m = [0] + [int(x) for x in rng.integers(0, 2, size=L - 1)]
+        ready = OP.group_ready_times(m, t)
+        normal_layers_in_arrival_order = [i for i in range(L - 1, -1, -1) if m[i] == 0]
+        assert ready == [running[L - 1 - i] for i in normal_layers_in_arrival_order]
+        assert ready[-1] == running[-1]
+        assert all(x <= y for x, y in zip(ready, ready[1:]))
+    assert OP.group_ready_times([], []) == []
+
+
 def test_group_and_layout_invariants():
     rng = np.random.default_rng(10)
     for _ in range(100):
