@@ -307,10 +307,15 @@ int mgwfbp_group_pipeline_span(mgwfbp_ctx* ctx, int32_t group_first, int32_t gro
  * issues ONE fused pack + reduce + update launch (as mgwfbp_group_pipeline_span) covering every group that is
  * full by then, on the next of `streams` in round-robin order, and repeats until all groups are launched; then
  * it waits for all the streams.  Groups that fill while the handler is busy launching are therefore batched
- * into the next launch, and a schedule faster than the launch rate degenerates into few, long launches.
- * Unlike the other device entry points this call BLOCKS until the work is done.
+ * into the next launch.  Unless max_groups_per_launch is 1 the handler also keeps at most two launches queued
+ * per stream: while a stream's earlier launches are still running it goes on collecting groups, so a schedule
+ * faster than the GPU degenerates into few, long launches instead of a long queue of small ones.
+ * Unlike the other device entry points this call BLOCKS until the work is done (and creates and destroys a
+ * few HIP events).
  *   group_ready_s  host [G]   e.g. from mgwfbp_group_ready_times; finite, >= 0, non-decreasing
  *   time_scale     >= 0; 1 replays the schedule in real time, 0 makes every group full at once
+ *   max_groups_per_launch  0 = no limit; 1 = strictly one launch per group (groups that are already full
+ *                  are then launched back to back), n = at most n groups per launch
  *   streams        host [n_streams] of hipStream_t, 1 <= n_streams <= 16, all of default priority; launches for
  *                  different groups touch disjoint elements, so they need no ordering among themselves
  *   stats_out      host [4] or NULL  out: [0] launches issued, [1] seconds from t0 at which the last group was
@@ -318,7 +323,7 @@ int mgwfbp_group_pipeline_span(mgwfbp_ctx* ctx, int32_t group_first, int32_t gro
  *                  the pipeline left exposed after the last gradient
  * Errors: MGWFBP_EINVAL, MGWFBP_EHIP. */
 int mgwfbp_handler_replay(mgwfbp_ctx* ctx, const double* group_ready_s, double time_scale,
-                          void* const* streams, int32_t n_streams,
+                          int32_t max_groups_per_launch, void* const* streams, int32_t n_streams,
                           const void* const* d_grad_ptrs, void* const* d_merge_bufs, float* d_reduced,
                           float* const* d_w_ptrs, float* const* d_v_ptrs, float lr, float momentum,
                           double* stats_out);

@@ -63,7 +63,7 @@ _SIGNATURES = {
     "mgwfbp_group_pipeline": (C.c_int, [_vp, C.c_int32, _vp, _vp, _vp, _vp, _vp, C.c_float, C.c_float, _vp]),
     "mgwfbp_direct_update": (C.c_int, [_vp, C.c_int32, _vp, _vp, _vp, _vp, C.c_float, C.c_float, _vp]),
     "mgwfbp_group_pipeline_span": (C.c_int, [_vp, C.c_int32, C.c_int32, _vp, _vp, _vp, _vp, _vp, C.c_float, C.c_float, _vp]),
-    "mgwfbp_handler_replay": (C.c_int, [_vp, _f64p, C.c_double, C.POINTER(_vp), C.c_int32, _vp, _vp, _vp, _vp, _vp,
+    "mgwfbp_handler_replay": (C.c_int, [_vp, _f64p, C.c_double, C.c_int32, C.POINTER(_vp), C.c_int32, _vp, _vp, _vp, _vp, _vp,
                                         C.c_float, C.c_float, _f64p]),
     "mgwfbp_last_hip_error": (C.c_int, []),
     "mgwfbp_version": (C.c_char_p, []),
@@ -318,8 +318,8 @@ class Context:
             self._h, int(group_first), int(group_count), _vp(d_grad_ptrs), _vp(d_merge_bufs), _vp(d_reduced or None),
             _vp(d_w_ptrs), _vp(d_v_ptrs), float(lr), float(momentum), _vp(stream)))
 
-    def handler_replay(self, group_ready_s: Sequence[float], time_scale: float, streams: Sequence[int],
-                       d_grad_ptrs: int, d_merge_bufs: int, d_reduced: int, d_w_ptrs: int, d_v_ptrs: int,
+    def handler_replay(self, group_ready_s: Sequence[float], time_scale: float, max_groups_per_launch: int,
+                       streams: Sequence[int], d_grad_ptrs: int, d_merge_bufs: int, d_reduced: int, d_w_ptrs: int, d_v_ptrs: int,
                        lr: float, momentum: float):
         """mgwfbp_handler_replay (blocks until the work is done) -> (launches, last_ready_s, done_s, exposed_s)."""
         ready = _arr(group_ready_s, np.float64)
@@ -328,6 +328,6 @@ class Context:
         table = (_vp * max(len(streams), 1))(*[int(x) for x in streams])
         stats = np.zeros(4, np.float64)
         _check("mgwfbp_handler_replay", lib().mgwfbp_handler_replay(
-            self._h, _ptr(ready, _f64p), float(time_scale), table, len(streams), _vp(d_grad_ptrs), _vp(d_merge_bufs),
+            self._h, _ptr(ready, _f64p), float(time_scale), int(max_groups_per_launch), table, len(streams), _vp(d_grad_ptrs), _vp(d_merge_bufs),
             _vp(d_reduced or None), _vp(d_w_ptrs), _vp(d_v_ptrs), float(lr), float(momentum), _ptr(stats, _f64p)))
         return int(stats[0]), float(stats[1]), float(stats[2]), float(stats[3])

@@ -1021,34 +1021,58 @@ int mgwfbp_group_pipeline_span(mgwfbp_ctx* c, int32_t group_first, int32_t group
                            hip_stream, &s);
 }
 
-int mgwfbp_handler_replay(mgwfbp_ctx* c, const double* group_ready_s, double time_scale, void* const* streams,
-                          int32_t n_streams, const void* const* d_grad_ptrs, void* const* d_merge_bufs,
+int mgwfbp_handler_replay(mgwfbp_ctx* c, const double* group_ready_s, double time_scale,
+                          int32_t max_groups_per_launch, void* const* streams, int32_t n_streams, const void* const* d_grad_ptrs, void* const* d_merge_bufs,
                           float* d_reduced, float* const* d_w_ptrs, float* const* d_v_ptrs, float lr, float momentum,
                           double* stats_out) {
     if (c == nullptr || !c->on_device || streams == nullptr || n_streams < 1 || n_streams > 16) return MGWFBP_EINVAL;
-    if (!std::isfinite(time_scale) || time_scale < 0.0) return MGWFBP_EINVAL;
+    if (!std::isfinite(time_scale) || time_scale < 0.0 || max_groups_per_launch < 0) return MGWFBP_EINVAL;
     const int32_t G = c->host.G;
     if (G > 0 && group_ready_s == nullptr) return MGWFBP_EINVAL;
     for (int32_t k = 0; k < G; ++k) {
         if (!std::isfinite(group_ready_s[k]) || group_ready_s[k] < 0.0) return MGWFBP_EINVAL;
         if (k > 0 && group_ready_s[k] < group_ready_s[k - 1]) return MGWFBP_EINVAL;
     }
+    // Back-pressure for the batching forms: at most two launches queued per stream.  While a stream's earlier
+    // launches are still running the GPU has work anyway, so the handler keeps collecting groups instead of
+    // queueing ever more small launches behind them.  (One event per queue slot; created and destroyed here.)
+    constexpr int DEPTH = 2;
+    const bool throttle = max_groups_per_launch != 1;
+    hipEvent_t slot_done[16 * DEPTH] = {};
+    int rc = MGWFBP_OK;
+    if (throttle) {
+        for (int32_t j = 0; j < n_streams * DEPTH && rc == MGWFBP_OK; ++j)
+            rc = note(hipEventCreateWithFlags(&slot_done[j], hipEventDisableTiming));
+    }
     typedef std::chrono::steady_clock Clock;
     const Clock::time_point t0 = Clock::now();
     auto since_t0 = [&]() { return std::chrono::duration<double>(Clock::now() - t0).count(); };
     int32_t next = 0, launches = 0;
-    int rc = MGWFBP_OK;
     while (next < G && rc == MGWFBP_OK) {
         const double due = time_scale * group_ready_s[next];
         double now = since_t0();
         while (now < due) now = since_t0();       // the backward pass has not produced this group yet
+        const int32_t j = launches % n_streams;
+        const int32_t slot = j * DEPTH + (launches / n_streams) % DEPTH;
+        if (throttle && launches >= n_streams * DEPTH) {
+            hipError_t q;
+            while ((q = hipEventQuery(slot_done[slot])) == hipErrorNotReady) {
+            }
+            if (q != hipSuccess) {
+                rc = note(q);
+                break;
+            }
+            now = since_t0();
+        }
         int32_t upto = next + 1;                  // everything that filled meanwhile goes into the same launch
-        while (upto < G && time_scale * group_ready_s[upto] <= now) ++upto;
+        while (upto < G && time_scale * group_ready_s[upto] <= now &&
+               (max_groups_per_launch == 0 || upto - next < max_groups_per_launch)) ++upto;
         Span s;
         s.t0 = c->host.group_tile[static_cast<size_t>(next)];
         s.t1 = c->host.group_tile[static_cast<size_t>(upto)];
         rc = run<K_PIPELINE>(c, 0, d_grad_ptrs, d_merge_bufs, d_reduced, d_w_ptrs, d_v_ptrs, lr, momentum,
-                             streams[launches % n_streams], &s);
+                             streams[j], &s);
+        if (rc == MGWFBP_OK && throttle) rc = note(hipEventRecord(slot_done[slot], static_cast<hipStream_t>(streams[j])));
         ++launches;
         next = upto;
     }
@@ -1057,6 +1081,8 @@ int mgwfbp_handler_replay(mgwfbp_ctx* c, const double* group_ready_s, double tim
         if (rc == MGWFBP_OK) rc = rj;
     }
     const double done = since_t0();
+    for (hipEvent_t e : slot_done)
+        if (e != nullptr) (void)hipEventDestroy(e);
     if (stats_out != nullptr) {
         const double last = G > 0 ? time_scale * group_ready_s[G - 1] : 0.0;
         stats_out[0] = static_cast<double>(launches);

@@ -168,8 +168,9 @@ class DeviceModel:
                                      self.w_ptrs.data_ptr(), self.v_ptrs.data_ptr(), lr, momentum, self._stream())
 
     def handler_replay(self, lr: float, momentum: float, group_ready_s, time_scale: float, streams,
-                       write_reduced: bool = False):
+                       write_reduced: bool = False, max_groups_per_launch: int = 0):
         """Blocks until done; `streams` are raw stream handles.  Returns the library's four statistics."""
-        return self.ctx.handler_replay(group_ready_s, time_scale, streams, self.grad_ptrs.data_ptr(),
+        return self.ctx.handler_replay(group_ready_s, time_scale, max_groups_per_launch, streams,
+                                       self.grad_ptrs.data_ptr(),
                                        self.merge_ptrs.data_ptr(), self.reduced.data_ptr() if write_reduced else 0,
                                        self.w_ptrs.data_ptr(), self.v_ptrs.data_ptr(), lr, momentum)
