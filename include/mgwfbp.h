@@ -301,6 +301,27 @@ int mgwfbp_group_pipeline_span(mgwfbp_ctx* ctx, int32_t group_first, int32_t gro
                                float* const* d_w_ptrs, float* const* d_v_ptrs,
                                float lr, float momentum, void* hip_stream);
 
+/* mgwfbp_group_pipeline for callers that must not allocate device memory: code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc.  The context may come from mgwfbp_ctx_create_host (no device
+ * allocation at all): instead of the context's own device tables the kernels read the group/offset/tile
+ * tables from a fixed array of MGWFBP_STATIC_TABLE_MAX_BYTES that is part of the loaded library on every GPU
+ * (held until the process ends).  The call copies the context's tables there in stream order (skipped when the
+ * same unchanged context was the last one used on this device and on this stream) and launches the same
+ * kernel with the same arguments otherwise; it calls no allocating routine.  Same results as
+ * mgwfbp_group_pipeline.
+ *   - Runs on the CURRENT device, whichever device the context was created on.
+ *   - Every call on one GPU shares that GPU's array: calls whose work may overlap in time (different streams
+ *     without ordering, different host threads) race unless they pass the same unchanged context.
+ *   - The context must stay alive and unchanged until the work has finished.
+ * Errors: MGWFBP_ECAPACITY if the model's tables (32 bytes per tile of 2048 elements + 16 bytes per non-empty
+ * tensor, each table rounded up to 256 bytes) exceed the array -- about 500 M elements; MGWFBP_EINVAL;
+ * MGWFBP_EHIP. */
+#define MGWFBP_STATIC_TABLE_MAX_BYTES (8u << 20)
+int mgwfbp_group_pipeline_static(mgwfbp_ctx* ctx, int32_t group, const void* const* d_grad_ptrs,
+                                 void* const* d_merge_bufs, float* d_reduced,
+                                 float* const* d_w_ptrs, float* const* d_v_ptrs,
+                                 float lr, float momentum, void* hip_stream);
+
 /* Algorithm 2's communication handler, driven by a recorded schedule instead of a live backward pass.
  * Group k's buffer counts as full at host time t0 + time_scale * group_ready_s[k], t0 being the moment of the
  * call.  The handler waits (spinning on the host's monotonic clock) until the next unlaunched group is full,

@@ -63,6 +63,7 @@ _SIGNATURES = {
     "mgwfbp_group_pipeline": (C.c_int, [_vp, C.c_int32, _vp, _vp, _vp, _vp, _vp, C.c_float, C.c_float, _vp]),
     "mgwfbp_direct_update": (C.c_int, [_vp, C.c_int32, _vp, _vp, _vp, _vp, C.c_float, C.c_float, _vp]),
     "mgwfbp_group_pipeline_span": (C.c_int, [_vp, C.c_int32, C.c_int32, _vp, _vp, _vp, _vp, _vp, C.c_float, C.c_float, _vp]),
+    "mgwfbp_group_pipeline_static": (C.c_int, [_vp, C.c_int32, _vp, _vp, _vp, _vp, _vp, C.c_float, C.c_float, _vp]),
     "mgwfbp_handler_replay": (C.c_int, [_vp, _f64p, C.c_double, C.c_int32, C.POINTER(_vp), C.c_int32, _vp, _vp, _vp, _vp, _vp,
                                         C.c_float, C.c_float, _f64p]),
     "mgwfbp_last_hip_error": (C.c_int, []),
@@ -317,6 +318,12 @@ class Context:
         _check("mgwfbp_group_pipeline_span", lib().mgwfbp_group_pipeline_span(
             self._h, int(group_first), int(group_count), _vp(d_grad_ptrs), _vp(d_merge_bufs), _vp(d_reduced or None),
             _vp(d_w_ptrs), _vp(d_v_ptrs), float(lr), float(momentum), _vp(stream)))
+
+    def group_pipeline_static(self, group: int, d_grad_ptrs: int, d_merge_bufs: int, d_reduced: int, d_w_ptrs: int,
+                              d_v_ptrs: int, lr: float, momentum: float, stream: int = 0) -> None:
+        _check("mgwfbp_group_pipeline_static", lib().mgwfbp_group_pipeline_static(
+            self._h, int(group), _vp(d_grad_ptrs), _vp(d_merge_bufs), _vp(d_reduced or None), _vp(d_w_ptrs),
+            _vp(d_v_ptrs), float(lr), float(momentum), _vp(stream)))
 
     def handler_replay(self, group_ready_s: Sequence[float], time_scale: float, max_groups_per_launch: int,
                        streams: Sequence[int], d_grad_ptrs: int, d_merge_bufs: int, d_reduced: int, d_w_ptrs: int, d_v_ptrs: int,

@@ -57,6 +57,13 @@
 #endif
 #define MGWFBP_MAXSEG 512   // segments per tile whose offsets are staged in LDS
 
+// Table space of mgwfbp_group_pipeline_static: one copy per GPU, held until the process ends.  Host code must
+// not pass this name to a kernel or a copy (on the host it is only a stand-in for the symbol); the device
+// address comes from hipGetSymbolAddress, once per device.  (No `used` attribute here: the compiler exports a
+// file-local device variable under a global symbol only when it sees host code refer to it, as
+// mgwfbp_group_pipeline_static does; marked `used` it stays a local symbol that the runtime cannot look up.)
+static __device__ __align__(256) unsigned char scratch[MGWFBP_STATIC_TABLE_MAX_BYTES];
+
 namespace {
 
 constexpr int BLOCK = MGWFBP_BLOCK;
@@ -873,6 +880,17 @@ int run(mgwfbp_ctx* c, int32_t group, const void* const* grad_ptrs, void* const*
     return launch_by_p<KIND, uint16_t>(A, grid, stream);
 }
 
+// Per device: where that GPU's copy of `scratch` lives and whose tables it holds.
+struct StaticSlot {
+    unsigned char* ptr = nullptr;
+    bool loaded = false;
+    uint64_t serial = 0;              // context serial of the tables last written there
+    hipStream_t stream = nullptr;     // ... and the stream the copy was ordered on
+};
+constexpr int MAX_STATIC_DEVICES = 64;
+StaticSlot g_static[MAX_STATIC_DEVICES];
+std::mutex g_static_mutex;
+
 }  // namespace
 
 extern "C" {
@@ -1019,6 +1037,55 @@ int mgwfbp_group_pipeline_span(mgwfbp_ctx* c, int32_t group_first, int32_t group
     s.t1 = c->host.group_tile[static_cast<size_t>(group_first + group_count)];
     return run<K_PIPELINE>(c, 0, d_grad_ptrs, d_merge_bufs, d_reduced, d_w_ptrs, d_v_ptrs, lr, momentum,
                            hip_stream, &s);
+}
+
+int mgwfbp_group_pipeline_static(mgwfbp_ctx* c, int32_t group, const void* const* d_grad_ptrs,
+                                 void* const* d_merge_bufs, float* d_reduced, float* const* d_w_ptrs,
+                                 float* const* d_v_ptrs, float lr, float momentum, void* hip_stream) {
+    if (c == nullptr) return MGWFBP_EINVAL;
+    const HostTables& h = c->host;
+    if (group < -1 || group >= h.G) return MGWFBP_EINVAL;
+    auto round256 = [](size_t x) { return (x + 255) & ~static_cast<size_t>(255); };
+    const size_t b_tiles = h.tiles.size() * sizeof(TileHdr), b_n = h.seg_n.size() * sizeof(uint32_t);
+    const size_t b_layer = h.seg_layer.size() * sizeof(int32_t), b_off = h.seg_off.size() * sizeof(uint64_t);
+    const size_t o_n = round256(b_tiles), o_layer = o_n + round256(b_n), o_off = o_layer + round256(b_layer);
+    if (o_off + round256(b_off) > MGWFBP_STATIC_TABLE_MAX_BYTES) return MGWFBP_ECAPACITY;
+    if (h.tiles.empty()) return MGWFBP_OK;
+
+    int dev = -1;
+    int rc = note(hipGetDevice(&dev));
+    if (rc != MGWFBP_OK) return rc;
+    if (dev < 0 || dev >= MAX_STATIC_DEVICES) return MGWFBP_EINVAL;
+    std::lock_guard<std::mutex> lock(g_static_mutex);
+    StaticSlot& slot = g_static[dev];
+    if (slot.ptr == nullptr) {                    // first call on this device: where does its copy live?
+        void* p = nullptr;
+        rc = note(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+        if (rc != MGWFBP_OK) return rc;
+        if (p == nullptr) return MGWFBP_EHIP;
+        slot.ptr = static_cast<unsigned char*>(p);
+    }
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    if (!(slot.loaded && slot.serial == c->serial && slot.stream == stream)) {
+        // The array still holds the previous call's tables: overwrite them, in stream order, with this model's.
+        slot.loaded = false;
+        const struct { size_t off, bytes; const void* src; } parts[4] = {
+            {0, b_tiles, h.tiles.data()}, {o_n, b_n, h.seg_n.data()},
+            {o_layer, b_layer, h.seg_layer.data()}, {o_off, b_off, h.seg_off.data()}};
+        for (const auto& part : parts) {
+            if (part.bytes == 0) continue;
+            rc = note(hipMemcpyAsync(slot.ptr + part.off, part.src, part.bytes, hipMemcpyHostToDevice, stream));
+            if (rc != MGWFBP_OK) return rc;
+        }
+        slot.loaded = true;
+        slot.serial = c->serial;
+        slot.stream = stream;
+    }
+    const DevTables T{reinterpret_cast<const TileHdr*>(slot.ptr), reinterpret_cast<const uint32_t*>(slot.ptr + o_n),
+                      reinterpret_cast<const int32_t*>(slot.ptr + o_layer),
+                      reinterpret_cast<const uint64_t*>(slot.ptr + o_off)};
+    return run<K_PIPELINE>(c, group, d_grad_ptrs, d_merge_bufs, d_reduced, d_w_ptrs, d_v_ptrs, lr, momentum,
+                           hip_stream, nullptr, &T);
 }
 
 int mgwfbp_handler_replay(mgwfbp_ctx* c, const double* group_ready_s, double time_scale,

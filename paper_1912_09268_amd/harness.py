@@ -167,6 +167,11 @@ class DeviceModel:
                                      self.reduced.data_ptr() if write_reduced else 0,
                                      self.w_ptrs.data_ptr(), self.v_ptrs.data_ptr(), lr, momentum, self._stream())
 
+    def group_pipeline_static(self, lr: float, momentum: float, group: int = -1, write_reduced: bool = True) -> None:
+        self.ctx.group_pipeline_static(group, self.grad_ptrs.data_ptr(), self.merge_ptrs.data_ptr(),
+                                       self.reduced.data_ptr() if write_reduced else 0,
+                                       self.w_ptrs.data_ptr(), self.v_ptrs.data_ptr(), lr, momentum, self._stream())
+
     def handler_replay(self, lr: float, momentum: float, group_ready_s, time_scale: float, streams,
                        write_reduced: bool = False, max_groups_per_launch: int = 0):
         """Blocks until done; `streams` are raw stream handles.  Returns the library's four statistics."""
