@@ -52,6 +52,12 @@ ALL_WORKLOADS = ("vgg16", "resnet50", "transformer", "tiny_layers", "toy_mlp")
 # source it was measured on: the key is the git blob hash of csrc/kernels.hip, and bench.py reports null when
 # the file has changed since.
 MEASURED_FABRIC_BYTES = {
+    "57d387aff7e086fac2210695098dc2187d12881e": {
+        ("vgg16", "pipeline"): 1.10731e+10,
+        ("resnet50", "pipeline"): 2.04576e+09,
+        ("transformer", "pipeline"): 1.61091e+10,
+        ("tiny_layers", "pipeline"): 1.88173e+09,
+    },
 }
 
 # The paper's own numbers (other hardware, whole training iterations over a network): context, not a target.
@@ -433,7 +439,8 @@ def measure_workload(name, args, scrub, headline: bool):
 
     cold = time_cold(step, scrub, args.steps, args.warmup)
     cold_ms = statistics.median(cold)
-    wall_b2b, ev_b2b = time_back_to_back(step, args.steps, args.warmup)
+    wall_b2b, ev_b2b = (float("nan"), float("nan")) if args.no_back_to_back else \
+        time_back_to_back(step, args.steps, args.warmup)
     E = p.total_elems
     bpe = bytes_per_element(mode, p.P, g)
     step_bytes = bpe * E
@@ -447,8 +454,9 @@ def measure_workload(name, args, scrub, headline: bool):
         "ms_per_step": round(cold_ms, 5), "ms_per_step_min": round(min(cold), 5),
         "ms_per_step_max": round(max(cold), 5), "GBps": round(gbps, 1),
         "frac_of_8TBps": round(gbps / HBM_PEAK_GBPS, 4),
-        "back_to_back": {"ms_per_step": round(wall_b2b, 5), "event_ms_per_step": round(ev_b2b, 5),
-                         "GBps": round(step_bytes / (wall_b2b * 1e-3) / 1e9, 1)},
+        "back_to_back": None if args.no_back_to_back else {
+            "ms_per_step": round(wall_b2b, 5), "event_ms_per_step": round(ev_b2b, 5),
+            "GBps": round(step_bytes / (wall_b2b * 1e-3) / 1e9, 1)},
         "plan_us": round(plan_us, 2), "plan_us_through_python_binding": round(plan_us_binding, 2),
     }
     if not args.no_launch_forms and mode == "pipeline" and G > 0:
@@ -488,6 +496,8 @@ def main() -> int:
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-launch-forms", action="store_true")
     ap.add_argument("--no-ceiling", action="store_true")
+    ap.add_argument("--no-back-to-back", action="store_true",
+                    help="skip the back-to-back loop (a profiler then sees cold launches only)")
     ap.add_argument("--blocks-per-cu", type=int, default=0)
     ap.add_argument("--xcd-contiguous", action="store_true")
     ap.add_argument("--tiles-per-workgroup", type=int, default=-1,
@@ -498,6 +508,10 @@ def main() -> int:
     ap.add_argument("--copy-calibration", type=float, default=0.0, metavar="GiB",
                     help="instead of the benchmark, run a plain device copy of this many GiB `--steps` times "
                          "(reference dispatch of known size for scaling rocprofv3's FETCH_SIZE / WRITE_SIZE)")
+    ap.add_argument("--probe-mix", default="", metavar="R,W,X",
+                    help="instead of the benchmark, run the bench aid's bare stream pattern with R read-only, W "
+                         "write-only and X updated arrays of 512 MiB each `--steps` times (reference dispatches "
+                         "for counter studies)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (the path is per-GPU; nothing is sharded or "
@@ -524,6 +538,27 @@ def main() -> int:
         print(json.dumps({"calibration": "plain device copy", "bytes_read": nbytes, "bytes_written": nbytes,
                           "launches": args.steps, "ms_per_copy": round(ms, 4),
                           "GBps": round(2 * nbytes / ms / 1e6, 1)}))
+        return 0
+
+    if args.probe_mix:
+        import bench_aid as A
+        mix = [int(x) for x in args.probe_mix.split(",")]
+        n = 128 << 20
+        tensors = [[torch.zeros(n, dtype=torch.float32, device="cuda") for _ in range(c)] for c in mix]
+        ptrs = [[t.data_ptr() for t in group] for group in tensors]
+        stream = int(torch.cuda.current_stream().cuda_stream)
+        A.stream_probe(ptrs[0], ptrs[1], ptrs[2], n, stream)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(args.steps):
+            A.stream_probe(ptrs[0], ptrs[1], ptrs[2], n, stream)
+        e1.record()
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / args.steps
+        nbytes = 4 * n * (mix[0] + mix[1] + 2 * mix[2])
+        print(json.dumps({"probe_mix": mix, "bytes_per_launch": nbytes, "launches": args.steps + 1,
+                          "ms_per_launch": round(ms, 4), "GBps": round(nbytes / ms / 1e6, 1)}))
         return 0
 
     scrub = Scrubber()

@@ -206,8 +206,9 @@ int mgwfbp_ctx_tables(const mgwfbp_ctx* ctx, int32_t* n_segments, void* tiles_ou
                       uint64_t* seg_off_out, uint32_t* seg_n_out, int32_t* seg_layer_out,
                       int32_t* group_tile_out);
 
-/* Launch shape.  By default a call launches one workgroup of 256 lanes per tile it covers (per 16 KiB of
- * each worker's data for mgwfbp_pack, which runs as P single-worker copies).
+/* Launch shape.  By default a call launches one workgroup of 256 lanes per tile it covers, or per two tiles
+ * when the gradients are binary32 and the model's tensors average 32 tiles or more (per 16 KiB of each
+ * worker's data for mgwfbp_pack, which runs as P single-worker copies).
  *   blocks_per_cu > 0        caps the grid at compute units * blocks_per_cu workgroups, which then stride
  *                            over the work; <= 0 restores the default
  *   xcd_contiguous != 0      renumbers workgroups so that each of the 8 accelerator dies walks one

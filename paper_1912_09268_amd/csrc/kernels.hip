@@ -320,7 +320,12 @@ __device__ __forceinline__ void do_one(const Args<GradT>& A, const WorkerPtrs<Gr
 // Measured with the memory-side cache emptied before every launch: worker by worker is 1-3 % faster for binary32
 // gradients; for 16-bit gradients, whose shares are half as long, all loads first is 1-2 % faster up to 4 vectors
 // per lane and would need more than 200 registers beyond that.
+// (-DMGWFBP_FORCE_ORDER=0 / =1 compiles one order for every type, for comparison runs.)
+#ifdef MGWFBP_FORCE_ORDER
+template <typename GradT, int U> constexpr bool worker_by_worker() { return MGWFBP_FORCE_ORDER != 0; }
+#else
 template <typename GradT, int U> constexpr bool worker_by_worker() { return sizeof(GradT) == 4 || U >= 8; }
+#endif
 
 // All loads first.
 template <int KIND, typename GradT, int PT, bool WVNT, int U>
@@ -847,9 +852,20 @@ int run(mgwfbp_ctx* c, int32_t group, const void* const* grad_ptrs, void* const*
     }
 
     // tiles per workgroup: PACK runs as single-worker copies, whose tiles are small (one stream in, one
-    // out), so it takes several tiles per workgroup to keep the dispatcher from being the limit
+    // out), so it takes several tiles per workgroup to keep the dispatcher from being the limit.  The other
+    // kinds take pairs of tiles (16 KiB stretches per array) when the gradients are binary32 and the tensors
+    // are long enough for most pairs to lie inside one tensor: measured 2-3 % faster on the DNN shapes and
+    // 4 % slower on a model of a thousand small tensors.
     int32_t tpw = c->tiles_per_wg;
-    if (tpw <= 0) tpw = (KIND == K_PACK) ? std::max(1, 16384 / (TILE * (c->dtype == MGWFBP_F32 ? 4 : 2))) : 1;
+    if (tpw <= 0) {
+        if (KIND == K_PACK) {
+            tpw = std::max(1, 16384 / (TILE * (c->dtype == MGWFBP_F32 ? 4 : 2)));
+        } else {
+            const size_t n_seg = c->host.seg_layer.size();
+            const bool long_tensors = n_seg > 0 && c->host.tiles.size() / n_seg >= 32;
+            tpw = (c->dtype == MGWFBP_F32 && long_tensors) ? 2 : 1;
+        }
+    }
     const int32_t units = (count + tpw - 1) / tpw;
     int grid = units;
     if (c->blocks_per_cu > 0 && c->n_cu > 0 && static_cast<int64_t>(c->n_cu) * c->blocks_per_cu < units)
