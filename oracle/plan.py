@@ -21,7 +21,8 @@ Readings taken where the paper leaves a choice:
 
 Parity pins live in tests/test_oracle_plan.py (hand-evaluated timelines, closed forms for the
 all-normal and all-merged plans, the paper's 200 KB / 400 KB example, exhaustive search,
-limit cases, a group-level timeline simulation written independently of Eq. 7).
+limit cases, a group-level timeline simulation written independently of Eq. 7; group ready times
+against the hand timeline and a library running sum).
 The group counts the paper prints for its simulated clusters (Sec. 6.4) need backward-time traces
 that are not available: parity unpinned for those.
 """
@@ -77,18 +78,15 @@ def comm_start_times(t_c1: list, t_b1: list, tau_b1: list) -> list:
 # Eq. 8 with the merge properties Eq. 12-14: iteration time of a given plan
 # ------------------------------------------------------------------------------------------
 
-def iteration_time(merged: Sequence[int], size_bytes: Sequence[int], t_backward: Sequence[float],
-                   a: float, b: float) -> float:
-    """t_iter - t_f for the plan `merged` (0-based, merged[i] = 1 iff layer i+1 is merged into i).
+def timeline(merged: Sequence[int], size_bytes: Sequence[int], t_backward: Sequence[float],
+             a: float, b: float) -> Tuple[list, list, list]:
+    """The wait-free backpropagation timeline of the plan `merged` (0-based flags, merged[i] = 1 iff layer i+1
+    is a merged-gradient layer): 1-based lists (tau_b, tau_c, t_c).
 
-    A merged layer has no communication of its own (Eq. 12), hands its bytes to the layer below
-    (Eq. 13), and the layer below may start as soon as both are ready (Eq. 14, which is Eq. 7 with
-    t_c^(l) = 0).  The iteration ends when layer 1's message ends (Eq. 8)."""
+    A merged layer has no communication of its own (Eq. 12: t_c = 0) and hands its bytes to the layer below
+    (Eq. 13); every other layer's message takes a + b x bytes (Eq. 10); backward passes start by Eq. 6 and
+    communications by Eq. 7, which for the layer below a merged one is Eq. 14."""
     L = len(size_bytes)
-    if L == 0:
-        return 0.0
-    if merged[0]:
-        raise ValueError("layer 1 cannot be a merged-gradient layer")
     m = _one_based(merged)
     p = _one_based(int(x) for x in size_bytes)
     t_b = _one_based(float(x) for x in t_backward)
@@ -100,6 +98,17 @@ def iteration_time(merged: Sequence[int], size_bytes: Sequence[int], t_backward:
         t_c[l] = 0.0 if m[l] == MERGED else allreduce_time(a, b, p[l])
     tau_b = backward_start_times(t_b)
     tau_c = comm_start_times(t_c, t_b, tau_b)
+    return tau_b, tau_c, t_c
+
+
+def iteration_time(merged: Sequence[int], size_bytes: Sequence[int], t_backward: Sequence[float],
+                   a: float, b: float) -> float:
+    """t_iter - t_f for the plan `merged`: the iteration ends when layer 1's message ends (Eq. 8)."""
+    if len(size_bytes) == 0:
+        return 0.0
+    if merged[0]:
+        raise ValueError("layer 1 cannot be a merged-gradient layer")
+    _, tau_c, t_c = timeline(merged, size_bytes, t_backward, a, b)
     return tau_c[1] + t_c[1]
 
 
@@ -120,29 +129,23 @@ def single_layer_time(size_bytes, t_backward, a, b) -> float:
 
 def plan_algorithm1(size_bytes: Sequence[int], t_backward: Sequence[float], a: float, b: float
                     ) -> List[int]:
-    """Algorithm 1, with the full re-evaluation of tau_c after every merge (O(L^2)).
+    """The plan Algorithm 1 finds, stated through the definitions it rests on (O(L^2)).
+
+    Layers are decided from L down to 2, every layer below the one under decision still normal.  Layer l
+    becomes a merged-gradient layer iff, on the timeline of the plan decided so far (Eq. 6 and Eq. 7 under
+    Eq. 12-14), the gradient of layer l-1 exists less than `a` after layer l could start to communicate:
+    tau_b^(l-1) + t_b^(l-1) - tau_c^(l) < a, the layer-type rule of Lemma 1 / Theorem 1 in the form in which
+    Algorithm 1 evaluates it (left to right, strict).  Layer 1 is always normal.
 
     Returns merged[0..L-1]; merged[0] is always 0."""
     L = len(size_bytes)
-    if L == 0:
-        return []
-    p = _one_based(int(x) for x in size_bytes)
     t_b = _one_based(float(x) for x in t_backward)
-    m = [None] + [NORMAL] * L
-    t_c = [None] * (L + 1)
-    for l in range(1, L + 1):
-        t_c[l] = allreduce_time(a, b, p[l])
-    tau_b = backward_start_times(t_b)
-    tau_c = comm_start_times(t_c, t_b, tau_b)
+    m = [NORMAL] * L                                  # m[l - 1] is the type of layer l
     for l in range(L, 1, -1):
+        tau_b, tau_c, _ = timeline(m, size_bytes, t_backward, a, b)
         if tau_b[l - 1] + t_b[l - 1] - tau_c[l] < a:
-            # procedure Merge: layer l gives up its message and its bytes to layer l-1
-            t_c[l] = 0.0
-            p[l - 1] = p[l - 1] + p[l]
-            t_c[l - 1] = allreduce_time(a, b, p[l - 1])
-            tau_c = comm_start_times(t_c, t_b, tau_b)
-            m[l] = MERGED
-    return m[1:]
+            m[l - 1] = MERGED
+    return m
 
 
 def merge_rule_holds(l: int, tau_b1: list, t_b1: list, tau_c1: list, a: float) -> bool:

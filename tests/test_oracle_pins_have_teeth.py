@@ -67,15 +67,18 @@ PLAN_MUTANTS = [
     ("comm_start_times", "max(tau_c[l + 1] + t_c1[l + 1], tau_b1[l] + t_b1[l])", "max(tau_c[l + 1], tau_b1[l] + t_b1[l])"),
     ("comm_start_times", "max(tau_c[l + 1] + t_c1[l + 1], tau_b1[l] + t_b1[l])", "min(tau_c[l + 1] + t_c1[l + 1], tau_b1[l] + t_b1[l])"),
     ("comm_start_times", "tau_c[L] = tau_b1[L] + t_b1[L]", "tau_c[L] = tau_b1[L]"),
-    ("iteration_time", "p[l - 1] = p[l - 1] + p[l]", "p[l - 1] = p[l - 1]"),
+    ("timeline", "p[l - 1] = p[l - 1] + p[l]", "p[l - 1] = p[l - 1]"),
+    ("timeline", "p[l - 1] = p[l - 1] + p[l]", "p[l - 1] = p[l]"),
     ("iteration_time", "return tau_c[1] + t_c[1]", "return tau_c[1]"),
-    ("iteration_time", "0.0 if m[l] == MERGED else", "allreduce_time(a, b, 0) if m[l] == MERGED else"),
+    ("timeline", "0.0 if m[l] == MERGED else", "allreduce_time(a, b, 0) if m[l] == MERGED else"),
+    ("timeline", "for l in range(L, 1, -1):", "for l in range(2, L + 1):"),
     ("plan_algorithm1", "- tau_c[l] < a", "- tau_c[l] <= a"),
     ("plan_algorithm1", "- tau_c[l] < a", "- tau_c[l] > a"),
     ("plan_algorithm1", "tau_b[l - 1] + t_b[l - 1] - tau_c[l] < a", "tau_b[l] + t_b[l] - tau_c[l] < a"),
-    ("plan_algorithm1", "t_c[l] = 0.0", "pass"),
-    ("plan_algorithm1", "t_c[l - 1] = allreduce_time(a, b, p[l - 1])", "pass"),
-    ("plan_algorithm1", "tau_c = comm_start_times(t_c, t_b, tau_b)\n            m[l] = MERGED", "m[l] = MERGED"),
+    ("plan_algorithm1", "tau_b[l - 1] + t_b[l - 1] - tau_c[l] < a", "tau_b[l - 1] + t_b[l - 1] - tau_c[l - 1] < a"),
+    ("plan_algorithm1", "timeline(m, size_bytes", "timeline([NORMAL] * L, size_bytes"),
+    ("plan_algorithm1", "m[l - 1] = MERGED", "m[l - 2] = MERGED"),
+    ("plan_algorithm1", "for l in range(L, 1, -1):", "for l in range(2, L + 1):"),
     ("plan_optimal", "start = F[i] if F[i] > ready[k] else ready[k]", "start = ready[k]"),
     ("plan_optimal", "prefix[k] - prefix[i]", "prefix[k] - prefix[i - 1]"),
     ("groups_in_arrival_order", "for l in range(L, 0, -1):", "for l in range(1, L + 1):"),
