@@ -467,7 +467,10 @@ def test_pack_tensors_rejects_bad_runs():
 # HIP graph: one launch per group captured once, replayed with eager work in between
 # ------------------------------------------------------------------------------------------
 
-def test_per_group_launches_replay_correctly_from_a_hip_graph():
+@pytest.mark.parametrize("fork", [1, 4])
+def test_per_group_launches_replay_correctly_from_a_hip_graph(fork):
+    """One launch per group recorded into a HIP graph, on one stream (fork = 1) or forked over four streams and
+    joined again (the form bench.py times); every replay is compared with the oracle's next step."""
     import torch
     import paper_1912_09268_amd as M
     from paper_1912_09268_amd import harness as H
@@ -484,10 +487,21 @@ def test_per_group_launches_replay_correctly_from_a_hip_graph():
         w_flat, v_flat = W.initial_weights_flat(prof), W.initial_momentum_flat(prof)
         dm.upload_weights(w_flat, v_flat)
         torch.cuda.synchronize()
+        side = [torch.cuda.Stream() for _ in range(fork)] if fork > 1 else []     # default priority
         graph = torch.cuda.CUDAGraph()
         with torch.cuda.graph(graph):                      # capture only: nothing runs here
-            for k in range(ctx.n_groups):
-                dm.group_pipeline(prof.lr, prof.momentum, k)
+            if fork == 1:
+                for k in range(ctx.n_groups):
+                    dm.group_pipeline(prof.lr, prof.momentum, k)
+            else:
+                origin = torch.cuda.current_stream()
+                for s in side:
+                    s.wait_stream(origin)
+                for k in range(ctx.n_groups):
+                    with torch.cuda.stream(side[k % fork]):
+                        dm.group_pipeline(prof.lr, prof.momentum, k)
+                for s in side:
+                    origin.wait_stream(s)
         grads = [W.split_by_layer(f, prof.n_elems) for f in flats]
         groups = OP.groups_in_arrival_order(merged)
         w_o = [x.copy() for x in W.split_by_layer(w_flat, prof.n_elems)]
