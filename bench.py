@@ -422,20 +422,22 @@ def measure_workload(name, args, scrub, headline: bool):
     def step():
         run_step(dm, mode, p.lr, p.momentum, G)
 
-    # tiles per workgroup: results never depend on the launch shape, so it is picked by timing a few cold
-    # steps, as a training loop can do during its first iterations
+    # Pacing (workgroups per compute unit): results never depend on it, so it is picked by timing a few cold
+    # steps, as a training loop can do during its first iterations.  "default" is the library's own choice.
+    ctx.set_launch(args.blocks_per_cu, args.xcd_contiguous, max(args.tiles_per_workgroup, 0))
     tuned = None
-    if args.tiles_per_workgroup < 0 and "per_group" not in mode:
-        best, tuned = 1, {}
-        for k in (1, 2, 4):
-            ctx.set_launch(args.blocks_per_cu, args.xcd_contiguous, k)
-            tuned[k] = round(statistics.median(time_cold(step, scrub, 7, 2)), 5)
-            if tuned[k] < tuned[best] * 0.995:          # prefer the smaller on a tie
+    if args.workgroups_per_cu == "auto" and "per_group" not in mode:
+        best, tuned = "default", {}
+        for k in ("default", 2, 3, 4):
+            ctx.set_pacing(0 if k == "default" else k, args.vectors_per_step)
+            tuned[str(k)] = round(statistics.median(time_cold(step, scrub, 7, 2)), 5)
+            if tuned[str(k)] < tuned[str(best)] * 0.995:      # prefer the earlier on a tie
                 best = k
-        tpw = best
+        wgs = best
     else:
-        tpw = max(args.tiles_per_workgroup, 0)
-    ctx.set_launch(args.blocks_per_cu, args.xcd_contiguous, tpw)
+        wgs = "default" if args.workgroups_per_cu in ("auto", "default") else int(args.workgroups_per_cu)
+    ctx.set_pacing(0 if wgs == "default" else wgs, args.vectors_per_step)
+    tpw = max(args.tiles_per_workgroup, 0)
 
     cold = time_cold(step, scrub, args.steps, args.warmup)
     cold_ms = statistics.median(cold)
@@ -450,7 +452,8 @@ def measure_workload(name, args, scrub, headline: bool):
         "workload": name, "tensors": p.L, "elements": E, "groups": G, "P": p.P,
         "dtype": "f32" if g == 4 else "bf16 gradients, f32 accumulate/update",
         "mode": mode, "launches_per_step": nl, "bytes_per_element": bpe, "bytes_per_step": step_bytes,
-        "tile_elems": ctx.tile_elems, "tiles_per_workgroup": tpw or "default", "autotune_cold_ms": tuned,
+        "tile_elems": ctx.tile_elems, "tiles_per_workgroup": tpw or "default", "workgroups_per_cu": wgs,
+        "vectors_per_step": args.vectors_per_step or "default", "autotune_cold_ms": tuned,
         "ms_per_step": round(cold_ms, 5), "ms_per_step_min": round(min(cold), 5),
         "ms_per_step_max": round(max(cold), 5), "GBps": round(gbps, 1),
         "frac_of_8TBps": round(gbps / HBM_PEAK_GBPS, 4),
@@ -462,6 +465,7 @@ def measure_workload(name, args, scrub, headline: bool):
     if not args.no_launch_forms and mode == "pipeline" and G > 0:
         res["launch_forms"] = launch_forms(dm, p, merged, G, scrub, cold_ms, max(5, args.steps // 3))
     if args.all_modes:
+        ctx.set_pacing(0, args.vectors_per_step)          # every other kind at the library's own pacing
         others = {}
         for m in ("pipeline", "direct", "pack", "reduce", "unpack_update", "reduce_update", "staged"):
             if m == mode:
@@ -500,9 +504,12 @@ def main() -> int:
                     help="skip the back-to-back loop (a profiler then sees cold launches only)")
     ap.add_argument("--blocks-per-cu", type=int, default=0)
     ap.add_argument("--xcd-contiguous", action="store_true")
-    ap.add_argument("--tiles-per-workgroup", type=int, default=-1,
-                    help="consecutive tiles per workgroup; 0 = library default, negative = pick 1, 2 or 4 by "
-                         "timing a few cold steps first")
+    ap.add_argument("--tiles-per-workgroup", type=int, default=0,
+                    help="consecutive tiles per workgroup; 0 = library default")
+    ap.add_argument("--workgroups-per-cu", default="auto",
+                    help="pacing: workgroups a compute unit may hold; 'auto' = pick among the library default, 2, 3 "
+                         "and 4 by timing a few cold steps first, 'default' = library default, n = fixed, -1 = no cap")
+    ap.add_argument("--vectors-per-step", type=int, default=0, help="pacing: 1 or 2; 0 = library default")
     ap.add_argument("--resident-mib", type=int, default=-1,
                     help="MiB of w+v kept cacheable (library default, 0, if negative)")
     ap.add_argument("--copy-calibration", type=float, default=0.0, metavar="GiB",
@@ -583,7 +590,8 @@ def main() -> int:
         "config": {"workload": args.workload, "tensors": head["tensors"], "elements": head["elements"],
                    "groups": head["groups"], "P": head["P"], "mode": args.mode, "launches_per_step": nl,
                    "bytes_per_element": head["bytes_per_element"], "tile_elems": head["tile_elems"],
-                   "tiles_per_workgroup": head["tiles_per_workgroup"], "autotune_cold_ms": head["autotune_cold_ms"],
+                   "tiles_per_workgroup": head["tiles_per_workgroup"], "workgroups_per_cu": head["workgroups_per_cu"],
+                   "vectors_per_step": head["vectors_per_step"], "autotune_cold_ms": head["autotune_cold_ms"],
                    "blocks_per_cu": args.blocks_per_cu or "default", "xcd_contiguous": bool(args.xcd_contiguous),
                    "timing": "median of %d steps, each between its own HIP events on the launch stream and each "
                              "preceded by an untimed 1 GiB cache scrub (512 MiB read + 512 MiB written)" % args.steps},

@@ -206,19 +206,27 @@ int mgwfbp_ctx_tables(const mgwfbp_ctx* ctx, int32_t* n_segments, void* tiles_ou
                       uint64_t* seg_off_out, uint32_t* seg_n_out, int32_t* seg_layer_out,
                       int32_t* group_tile_out);
 
-/* Launch shape.  By default a call launches one workgroup of 256 lanes per tile it covers, or per two tiles
- * when the gradients are binary32 and the model's tensors average 32 tiles or more (per 16 KiB of each
+/* Launch shape.  By default a call launches one workgroup of 256 lanes per tile it covers (per 16 KiB of each
  * worker's data for mgwfbp_pack, which runs as P single-worker copies).
  *   blocks_per_cu > 0        caps the grid at compute units * blocks_per_cu workgroups, which then stride
  *                            over the work; <= 0 restores the default
  *   xcd_contiguous != 0      renumbers workgroups so that each of the 8 accelerator dies walks one
  *                            contiguous eighth of the range instead of every eighth piece
- *   tiles_per_workgroup > 0  consecutive tiles a workgroup handles per turn; with 2 (4) or more, two (four)
- *                            consecutive full tiles of one tensor are taken together as one longer chunk;
- *                            <= 0 restores the default
+ *   tiles_per_workgroup > 0  consecutive tiles a workgroup handles, one after the other; <= 0 restores the
+ *                            default
  * Results never depend on the launch shape. */
 int mgwfbp_ctx_set_launch(mgwfbp_ctx* ctx, int32_t blocks_per_cu, int32_t xcd_contiguous,
                           int32_t tiles_per_workgroup);
+
+/* Pacing.  The kernels walk a tile in steps of `vectors_per_step` 16-byte vectors per lane, one worker at a
+ * time, so that a workgroup has vectors_per_step x 4 KiB of loads in flight (half that for 16-bit gradients),
+ * and a launch asks for enough (unused) LDS that at most `workgroups_per_cu` workgroups share a compute unit.
+ * Their product is the load traffic a compute unit keeps in flight; MI355X serves the mixes of this library
+ * fastest at about 16 KiB and about a tenth slower beyond 20 KiB.
+ *   workgroups_per_cu  2..7 = cap; 0 = the library's default for the kind of kernel; < 0 or >= 8 = no cap
+ *   vectors_per_step   1 or 2; 0 = the library's default
+ * Results never depend on it. */
+int mgwfbp_ctx_set_pacing(mgwfbp_ctx* ctx, int32_t workgroups_per_cu, int32_t vectors_per_step);
 
 /* How many bytes of weights + momenta (8 per element, counted from the start of the arena) are accessed
  * with ordinary loads and stores so that they stay in the GPU's 256 MB memory-side cache from one

@@ -44,6 +44,7 @@
 #include <chrono>
 #include <cmath>
 #include <cstdint>
+#include <cstdlib>
 #include <cstring>
 #include <mutex>
 #include <new>
@@ -55,7 +56,7 @@
 #define MGWFBP_NT 3   // bit 0: non-temporal loads of gradients / merge / reduced, bit 1: non-temporal
                       // stores to merge / reduced, bit 2: non-temporal accesses to w and v
 #endif
-#define MGWFBP_MAXSEG 512   // segments per tile whose offsets are staged in LDS
+#define MGWFBP_MAXSEG (2 * MGWFBP_BLOCK)   // segments per tile whose offsets are staged in LDS (two per lane)
 
 // Table space of mgwfbp_group_pipeline_static: one copy per GPU, held until the process ends.  Host code must
 // not pass this name to a kernel or a copy (on the host it is only a stand-in for the symbol); the device
@@ -186,112 +187,129 @@ template <typename T> struct WorkerPtrs<T, 0> {
     __device__ __forceinline__ T* get(int w) const { return ro(base)[w * stride]; }
 };
 
-// Everything one lane holds between its loads and its stores for one vector (W = 4) or element (W = 1).
-template <typename GradT, int PT, int W> struct Regs {
-    typename VecOf<GradT, W>::type g[PT > 0 ? PT : 1];
-    typename VecOf<float, W>::type r, w, v;
-};
+// ---------------------------------------------------------------------------------------------
+// one paced step: N vectors (W = 4) or one element (W = 1) per lane, at arena position `apos`, which is
+// element `soff` of its tensor; the N vectors lie `stride` elements apart
+// ---------------------------------------------------------------------------------------------
+//
+// The step is taken worker by worker: load one worker's values, store them into that worker's merge arena
+// (kinds that fill the arenas), add them to the running sums -- acc = g_0, then acc = acc + g_w, the worker
+// order 0..P-1 of Eq. 2 -- and go on to the next worker; then the reduced arena, then v, then w.  A lane never
+// has more than N loads in flight (kinds without stores between the workers take MGWFBP_READ_GROUP workers at a
+// time), and that is the point: the memory system serves this traffic fastest when each compute unit keeps only
+// about 16 KiB of loads in flight, and collapses by a tenth beyond about 20 KiB.  N x 4 KiB per workgroup times
+// the workgroups a compute unit is allowed to hold (see run()) sets that budget.
+#ifndef MGWFBP_READ_GROUP
+#define MGWFBP_READ_GROUP 2
+#endif
 
-// ---------------------------------------------------------------------------------------------
-// load phase / store phase for one vector or element at arena position `apos`, which is element
-// `soff` of its tensor
-// ---------------------------------------------------------------------------------------------
-template <int KIND, typename GradT, int PT, int W, bool WVNT>
-__device__ __forceinline__ void load_phase(Regs<GradT, PT, W>& R, const Args<GradT>& A,
-                                           const WorkerPtrs<const GradT, PT>& src,
-                                           const WorkerPtrs<GradT, PT>& mrg,
-                                           const float* wp, const float* vp, int64_t soff, int64_t apos) {
+// keeps the compiler from moving the next group's loads above this group's arithmetic
+__device__ __forceinline__ void pace() { __builtin_amdgcn_sched_barrier(0); }
+
+template <int KIND, typename GradT, int PT, int W, int N, bool WVNT, bool TOGETHER = false>
+__device__ __forceinline__ void paced_step(const Args<GradT>& A, const WorkerPtrs<const GradT, PT>& src,
+                                           const WorkerPtrs<GradT, PT>& mrg, float* wp, float* vp,
+                                           int64_t soff, int64_t apos, int stride) {
     typedef typename VecOf<GradT, W>::type GV;
     typedef typename VecOf<float, W>::type FV;
-    if constexpr (PT > 0) {
-        if constexpr (reads_grads(KIND)) {
+    constexpr int C = Lanes<GV>::n;
+    FV acc[N];
+    if constexpr (reads_grads(KIND) || reads_merge(KIND)) {
+        // workers whose loads are issued together: one (kinds that store each worker's share before the next
+        // load), MGWFBP_READ_GROUP (kinds that only read them), or all of them / four at a time (TOGETHER: the
+        // general path, whose lanes also have to fetch their own pointers and gain from overlapping all of that)
+        constexpr int GW = TOGETHER ? (PT > 0 ? PT : 4) : (writes_merge(KIND) ? 1 : MGWFBP_READ_GROUP);
+        auto some_workers = [&](int w0, int count) {      // workers w0 .. w0 + count - 1, count <= GW
+            GV g[GW][N];
 #pragma unroll
-            for (int w = 0; w < PT; ++w) R.g[w] = ld<NT_LD, GV>(src.get(w) + soff);
-        } else if constexpr (reads_merge(KIND)) {
+            for (int j = 0; j < GW; ++j) {
+                if (j < count) {
+                    const GradT* from;
+                    if constexpr (reads_grads(KIND)) from = src.get(w0 + j) + soff;
+                    else from = mrg.get(w0 + j) + apos;
 #pragma unroll
-            for (int w = 0; w < PT; ++w) R.g[w] = ld<NT_LD, GV>(mrg.get(w) + apos);
-        }
-    }
-    if constexpr (KIND == K_UPDATE) R.r = ld<NT_LD, FV>(A.reduced + apos);
-    if constexpr (updates(KIND)) {
-        R.w = ld<WVNT, FV>(wp + soff);
-        R.v = ld<WVNT, FV>(vp + soff);
-    }
-}
-
-template <int KIND, typename GradT, int PT, int W, bool WVNT>
-__device__ __forceinline__ void store_phase(Regs<GradT, PT, W>& R, const Args<GradT>& A,
-                                            const WorkerPtrs<const GradT, PT>& src,
-                                            const WorkerPtrs<GradT, PT>& mrg,
-                                            float* wp, float* vp, int64_t soff, int64_t apos) {
-    typedef typename VecOf<GradT, W>::type GV;
-    typedef typename VecOf<float, W>::type FV;
-    constexpr int N = Lanes<GV>::n;
-    if constexpr (PT > 0) {
-        if constexpr (writes_merge(KIND)) {
-#pragma unroll
-            for (int w = 0; w < PT; ++w) st<NT_ST, GV>(mrg.get(w) + apos, R.g[w]);
-        }
-        if constexpr (sums(KIND)) {
-#pragma unroll
-            for (int c = 0; c < N; ++c) {
-                float s = widen(comp(R.g[0], c));
-#pragma unroll
-                for (int w = 1; w < PT; ++w) s = s + widen(comp(R.g[w], c));   // worker order 0..P-1
-                setc(R.r, c, s * A.inv_p);
-            }
-        }
-    } else {
-        // any P: take the workers four at a time (four loads in flight), accumulating in worker order
-        FV acc;
-        for (int w0 = 0; w0 < A.P; w0 += 4) {
-            GV g[4];
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                if (w0 + j < A.P) {
-                    if constexpr (reads_grads(KIND)) g[j] = ld<NT_LD, GV>(src.get(w0 + j) + soff);
-                    else if constexpr (reads_merge(KIND)) g[j] = ld<NT_LD, GV>(mrg.get(w0 + j) + apos);
+                    for (int i = 0; i < N; ++i) g[j][i] = ld<NT_LD, GV>(from + i * stride);
                 }
             }
 #pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                if (w0 + j < A.P) {
-                    if constexpr (writes_merge(KIND)) st<NT_ST, GV>(mrg.get(w0 + j) + apos, g[j]);
+            for (int j = 0; j < GW; ++j) {
+                if (j < count) {
+                    if constexpr (writes_merge(KIND)) {
+                        GradT* to = mrg.get(w0 + j) + apos;
+#pragma unroll
+                        for (int i = 0; i < N; ++i) st<NT_ST, GV>(to + i * stride, g[j][i]);
+                    }
                     if constexpr (sums(KIND)) {
 #pragma unroll
-                        for (int c = 0; c < N; ++c) {
-                            const float x = widen(comp(g[j], c));
-                            setc(acc, c, (w0 + j) == 0 ? x : comp(acc, c) + x);
-                        }
+                        for (int i = 0; i < N; ++i)
+#pragma unroll
+                            for (int c = 0; c < C; ++c) {
+                                const float x = widen(comp(g[j][i], c));
+                                setc(acc[i], c, (w0 + j == 0) ? x : comp(acc[i], c) + x);
+                            }
                     }
                 }
             }
+        };
+        if constexpr (PT > 0) {
+#pragma unroll
+            for (int w0 = 0; w0 < PT; w0 += GW) {
+                some_workers(w0, PT - w0 < GW ? PT - w0 : GW);
+                pace();
+            }
+        } else {
+            for (int w0 = 0; w0 < A.P; w0 += GW) {
+                some_workers(w0, A.P - w0 < GW ? A.P - w0 : GW);
+                pace();
+            }
         }
         if constexpr (sums(KIND)) {
 #pragma unroll
-            for (int c = 0; c < N; ++c) setc(R.r, c, comp(acc, c) * A.inv_p);
+            for (int i = 0; i < N; ++i)
+#pragma unroll
+                for (int c = 0; c < C; ++c) setc(acc[i], c, comp(acc[i], c) * A.inv_p);
         }
+    }
+    if constexpr (KIND == K_UPDATE) {
+#pragma unroll
+        for (int i = 0; i < N; ++i) acc[i] = ld<NT_LD, FV>(A.reduced + apos + i * stride);
     }
     if constexpr (writes_reduced(KIND)) {
-        if (KIND == K_REDUCE || A.reduced != nullptr) st<NT_ST, FV>(A.reduced + apos, R.r);
+        if (KIND == K_REDUCE || A.reduced != nullptr) {
+#pragma unroll
+            for (int i = 0; i < N; ++i) st<NT_ST, FV>(A.reduced + apos + i * stride, acc[i]);
+        }
     }
     if constexpr (updates(KIND)) {
-        FV wn, vn;
+        FV v[N];
 #pragma unroll
-        for (int c = 0; c < N; ++c) {
-            const float t1 = A.mu * comp(R.v, c);
-            const float v1 = t1 + comp(R.r, c);
-            const float t2 = A.lr * v1;
-            const float w1 = comp(R.w, c) - t2;
-            setc(vn, c, v1);
-            setc(wn, c, w1);
+        for (int i = 0; i < N; ++i) v[i] = ld<WVNT, FV>(vp + soff + i * stride);
+#pragma unroll
+        for (int i = 0; i < N; ++i) {
+#pragma unroll
+            for (int c = 0; c < C; ++c) {
+                const float t1 = A.mu * comp(v[i], c);
+                setc(v[i], c, t1 + comp(acc[i], c));
+            }
+            st<WVNT, FV>(vp + soff + i * stride, v[i]);
         }
-        st<WVNT, FV>(vp + soff, vn);
-        st<WVNT, FV>(wp + soff, wn);
+        if constexpr (!TOGETHER) pace();
+        FV w[N];
+#pragma unroll
+        for (int i = 0; i < N; ++i) w[i] = ld<WVNT, FV>(wp + soff + i * stride);
+#pragma unroll
+        for (int i = 0; i < N; ++i) {
+#pragma unroll
+            for (int c = 0; c < C; ++c) {
+                const float t2 = A.lr * comp(v[i], c);
+                setc(w[i], c, comp(w[i], c) - t2);
+            }
+            st<WVNT, FV>(wp + soff + i * stride, w[i]);
+        }
     }
 }
 
-// one vector or element, loads then stores (general path)
+// one vector or element of the general path
 template <int KIND, typename GradT, int PT, int W>
 __device__ __forceinline__ void do_one(const Args<GradT>& A, const WorkerPtrs<GradT, PT>& mrg,
                                        int layer, int64_t soff, int64_t apos) {
@@ -303,134 +321,17 @@ __device__ __forceinline__ void do_one(const Args<GradT>& A, const WorkerPtrs<Gr
         wp = ro(A.w_ptrs)[layer];
         vp = ro(A.v_ptrs)[layer];
     }
-    Regs<GradT, PT, W> R;
-    load_phase<KIND, GradT, PT, W, NT_WV>(R, A, src, mrg, wp, vp, soff, apos);
-    store_phase<KIND, GradT, PT, W, NT_WV>(R, A, src, mrg, wp, vp, soff, apos);
+    paced_step<KIND, GradT, PT, W, 1, NT_WV, true>(A, src, mrg, wp, vp, soff, apos, 0);
 }
 
 // ---------------------------------------------------------------------------------------------
-// fast path: the whole tile belongs to one tensor
+// fast path: `nvec` vectors per lane (one or more whole tiles) that lie inside one tensor, taken STEPV
+// vectors at a time; vector u of the chunk covers elements u * BLOCK * VEC + lane * VEC ...
 // ---------------------------------------------------------------------------------------------
-// Order of the memory instructions of a fast tile:
-//   all loads first   every load of the chunk (P gradient vectors + w + v per vector) before its first store;
-//   worker by worker  load one worker's share of the chunk, store it into that worker's merge arena, add it to
-//                     the running sums, go on to the next worker; w and v come last.  At any moment a workgroup
-//                     then reads one array and writes one array, U * 4 KiB (binary32) of each at a stretch, and
-//                     a lane holds the running sums and one worker's share instead of all P.
-// Measured with the memory-side cache emptied before every launch: worker by worker is 1-3 % faster for binary32
-// gradients; for 16-bit gradients, whose shares are half as long, all loads first is 1-2 % faster up to 4 vectors
-// per lane and would need more than 200 registers beyond that.
-// (-DMGWFBP_FORCE_ORDER=0 / =1 compiles one order for every type, for comparison runs.)
-#ifdef MGWFBP_FORCE_ORDER
-template <typename GradT, int U> constexpr bool worker_by_worker() { return MGWFBP_FORCE_ORDER != 0; }
-#else
-template <typename GradT, int U> constexpr bool worker_by_worker() { return sizeof(GradT) == 4 || U >= 8; }
-#endif
-
-// All loads first.
-template <int KIND, typename GradT, int PT, bool WVNT, int U>
-__device__ __forceinline__ void fast_chunk_all_loads_first(const Args<GradT>& A, const WorkerPtrs<const GradT, PT>& src,
-                                                           const WorkerPtrs<GradT, PT>& mrg, float* wp, float* vp,
-                                                           int64_t tensor_off, int64_t tile_base) {
-    Regs<GradT, PT, VEC> R[U];
-    const int lane_elem = static_cast<int>(threadIdx.x) * VEC;
-#pragma unroll
-    for (int u = 0; u < U; ++u) {
-        const int p = u * (BLOCK * VEC) + lane_elem;
-        load_phase<KIND, GradT, PT, VEC, WVNT>(R[u], A, src, mrg, wp, vp, tensor_off + p, tile_base + p);
-    }
-#pragma unroll
-    for (int u = 0; u < U; ++u) {
-        const int p = u * (BLOCK * VEC) + lane_elem;
-        store_phase<KIND, GradT, PT, VEC, WVNT>(R[u], A, src, mrg, wp, vp, tensor_off + p, tile_base + p);
-    }
-}
-
-// Worker by worker.  The sums are taken in worker order, acc = g_0, then acc = acc + g_w, exactly as in
-// store_phase, so both orders give the same bits.
-template <int KIND, typename GradT, int PT, bool WVNT, int U>
-__device__ __forceinline__ void fast_chunk_worker_by_worker(const Args<GradT>& A, const WorkerPtrs<const GradT, PT>& src,
-                                                            const WorkerPtrs<GradT, PT>& mrg, float* wp, float* vp,
-                                                            int64_t tensor_off, int64_t tile_base) {
-    typedef typename VecOf<GradT, VEC>::type GV;
-    constexpr int STEP = BLOCK * VEC;
-    const int lane_elem = static_cast<int>(threadIdx.x) * VEC;
-    const int64_t soff = tensor_off + lane_elem;    // this lane's first element: in its tensor
-    const int64_t apos = tile_base + lane_elem;     //                            in the arena
-    f32x4 acc[U];
-    if constexpr (reads_grads(KIND) || reads_merge(KIND)) {
-        auto one_worker = [&](int w) {
-            const GradT* from;
-            if constexpr (reads_grads(KIND)) from = src.get(w) + soff;
-            else from = mrg.get(w) + apos;
-            GV g[U];
-#pragma unroll
-            for (int u = 0; u < U; ++u) g[u] = ld<NT_LD, GV>(from + u * STEP);
-            if constexpr (writes_merge(KIND)) {
-                GradT* to = mrg.get(w) + apos;
-#pragma unroll
-                for (int u = 0; u < U; ++u) st<NT_ST, GV>(to + u * STEP, g[u]);
-            }
-            if constexpr (sums(KIND)) {
-#pragma unroll
-                for (int u = 0; u < U; ++u)
-#pragma unroll
-                    for (int c = 0; c < VEC; ++c) {
-                        const float x = widen(g[u][c]);
-                        acc[u][c] = (w == 0) ? x : acc[u][c] + x;
-                    }
-            }
-        };
-        if constexpr (PT > 0) {
-#pragma unroll
-            for (int w = 0; w < PT; ++w) one_worker(w);
-        } else {
-            for (int w = 0; w < A.P; ++w) one_worker(w);
-        }
-        if constexpr (sums(KIND)) {
-#pragma unroll
-            for (int u = 0; u < U; ++u)
-#pragma unroll
-                for (int c = 0; c < VEC; ++c) acc[u][c] = acc[u][c] * A.inv_p;
-        }
-    }
-    if constexpr (KIND == K_UPDATE) {
-#pragma unroll
-        for (int u = 0; u < U; ++u) acc[u] = ld<NT_LD, f32x4>(A.reduced + apos + u * STEP);
-    }
-    if constexpr (writes_reduced(KIND)) {
-        if (KIND == K_REDUCE || A.reduced != nullptr) {
-#pragma unroll
-            for (int u = 0; u < U; ++u) st<NT_ST, f32x4>(A.reduced + apos + u * STEP, acc[u]);
-        }
-    }
-    if constexpr (updates(KIND)) {
-        f32x4 v[U], w[U];
-#pragma unroll
-        for (int u = 0; u < U; ++u) v[u] = ld<WVNT, f32x4>(vp + soff + u * STEP);
-#pragma unroll
-        for (int u = 0; u < U; ++u) w[u] = ld<WVNT, f32x4>(wp + soff + u * STEP);
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-#pragma unroll
-            for (int c = 0; c < VEC; ++c) {
-                const float t1 = A.mu * v[u][c];
-                const float v1 = t1 + acc[u][c];
-                const float t2 = A.lr * v1;
-                v[u][c] = v1;
-                w[u][c] = w[u][c] - t2;
-            }
-            st<WVNT, f32x4>(vp + soff + u * STEP, v[u]);
-        }
-#pragma unroll
-        for (int u = 0; u < U; ++u) st<WVNT, f32x4>(wp + soff + u * STEP, w[u]);
-    }
-}
-
-// RUN consecutive tiles that lie inside the same tensor, handled as one chunk of RUN * TVECS vectors per lane.
-template <int KIND, typename GradT, int PT, bool WVNT, int RUN>
-__device__ __forceinline__ void fast_tiles(const Args<GradT>& A, const WorkerPtrs<GradT, PT>& mrg,
-                                           int layer, int64_t tensor_off, int64_t tile_base) {
+template <int KIND, typename GradT, int PT, bool WVNT, int STEPV>
+__device__ __forceinline__ void fast_chunk(const Args<GradT>& A, const WorkerPtrs<GradT, PT>& mrg,
+                                           int layer, int64_t tensor_off, int64_t tile_base, int nvec) {
+    static_assert(TVECS % STEPV == 0, "a tile is a whole number of steps");
     WorkerPtrs<const GradT, PT> src;
     float* wp = nullptr;
     float* vp = nullptr;
@@ -439,28 +340,15 @@ __device__ __forceinline__ void fast_tiles(const Args<GradT>& A, const WorkerPtr
         wp = ro(A.w_ptrs)[layer];
         vp = ro(A.v_ptrs)[layer];
     }
-    if constexpr (worker_by_worker<GradT, RUN * TVECS>() || KIND == K_UPDATE)
-        fast_chunk_worker_by_worker<KIND, GradT, PT, WVNT, RUN * TVECS>(A, src, mrg, wp, vp, tensor_off, tile_base);
-    else
-        fast_chunk_all_loads_first<KIND, GradT, PT, WVNT, RUN * TVECS>(A, src, mrg, wp, vp, tensor_off, tile_base);
-}
-
-template <int KIND, typename GradT, int PT, bool WVNT, int MAXRUN>
-__device__ __forceinline__ void fast_run(int run, const Args<GradT>& A, const WorkerPtrs<GradT, PT>& mrg,
-                                         int layer, int64_t tensor_off, int64_t tile_base) {
-    if constexpr (MAXRUN >= 4) {
-        if (run == 4) {
-            fast_tiles<KIND, GradT, PT, WVNT, 4>(A, mrg, layer, tensor_off, tile_base);
-            return;
-        }
+    constexpr int STEP = BLOCK * VEC;
+    const int lane_elem = static_cast<int>(threadIdx.x) * VEC;
+    const int64_t soff = tensor_off + lane_elem;    // this lane's first element: in its tensor
+    const int64_t apos = tile_base + lane_elem;     //                            in the arena
+    for (int u = 0; u < nvec; u += STEPV) {
+        paced_step<KIND, GradT, PT, VEC, STEPV, WVNT>(A, src, mrg, wp, vp, soff + static_cast<int64_t>(u) * STEP,
+                                                      apos + static_cast<int64_t>(u) * STEP, STEP);
+        pace();
     }
-    if constexpr (MAXRUN >= 2) {
-        if (run == 2) {
-            fast_tiles<KIND, GradT, PT, WVNT, 2>(A, mrg, layer, tensor_off, tile_base);
-            return;
-        }
-    }
-    fast_tiles<KIND, GradT, PT, WVNT, 1>(A, mrg, layer, tensor_off, tile_base);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -573,10 +461,8 @@ __device__ __forceinline__ TileHdr load_header(const TileHdr* p) {
     return h;
 }
 
-// MAXRUN (1, 2 or 4): how many consecutive full tiles of one tensor a workgroup may take together as one chunk.
-// It is a template parameter because the registers a kernel is given are those of its hungriest path: a
-// launch that never fuses tiles should not pay (in waves per SIMD) for the long-chunk path.
-template <int KIND, typename GradT, int PT, int MAXRUN>
+// STEPV (1 or 2): vectors per lane a fast tile is walked in (see paced_step).
+template <int KIND, typename GradT, int PT, int STEPV>
 __global__ void __launch_bounds__(MGWFBP_BLOCK) mgwfbp_stream_kernel(const Args<GradT> A) {
     __shared__ int s_loc[MAXSEG + 1];
     __shared__ int s_layer[MAXSEG];
@@ -604,8 +490,7 @@ __global__ void __launch_bounds__(MGWFBP_BLOCK) mgwfbp_stream_kernel(const Args<
     }
     for (int u = u_begin; u < u_end; u += u_step) {
         const int t_end = min((u + 1) * K, A.tile_count);
-        int t = u * K;
-        while (t < t_end) {
+        for (int t = u * K; t < t_end; ++t) {
             const int tile = A.tile_first + t;
             const TileHdr h = load_header(A.tiles + tile);
             const int64_t tile_base = static_cast<int64_t>(tile) * TILE;
@@ -614,30 +499,13 @@ __global__ void __launch_bounds__(MGWFBP_BLOCK) mgwfbp_stream_kernel(const Args<
                 const int64_t l = A.clip_lo - tile_base, r = A.clip_hi - tile_base;
                 if (l > 0) clo = l < h.valid ? static_cast<int>(l) : h.valid;
                 if (r < h.valid) chi = r > 0 ? static_cast<int>(r) : 0;
-                if (chi <= clo) {
-                    ++t;
-                    continue;
-                }
+                if (chi <= clo) continue;
             }
             if (!(clo == 0 && chi == TILE && (!needs_owner(KIND) || h.nseg == 1))) {
                 general_tile<KIND, GradT, PT>(A, mrg, h, tile_base, clo, chi, s_loc, s_layer, s_wave);
-                ++t;
                 continue;
             }
-            // A full tile inside one tensor.  If the workgroup has more tiles to do and the next one (or the
-            // next three) are full tiles of the same tensor with the same cache policy, they are taken
-            // together as one longer chunk (same work per element, longer stretches per array).
-            int run = 1;
-            if (MAXRUN > 1 && !A.clipped && t + 1 < t_end) {
-                const int left = t_end - t;
-                const TileHdr h1 = load_header(A.tiles + tile + 1);
-                const TileHdr h2 = load_header(A.tiles + tile + (left > 2 ? 2 : 1));
-                const TileHdr h3 = load_header(A.tiles + tile + (left > 3 ? 3 : 1));
-                auto joins = [&](const TileHdr& x) {
-                    return x.valid == TILE && x.flags == h.flags && (!needs_owner(KIND) || (x.nseg == 1 && x.layer0 == h.layer0));
-                };
-                if (joins(h1)) run = (MAXRUN >= 4 && left >= 4 && joins(h2) && joins(h3)) ? 4 : 2;
-            }
+            // A full tile inside one tensor.
             // Tiles flagged "resident" keep their w and v in the memory-side cache between iterations
             // (ordinary loads and stores); all other w, v traffic is streamed past it like the gradients.
             // The two arms differ only in the cache policy of their memory instructions; the empty asm
@@ -645,14 +513,13 @@ __global__ void __launch_bounds__(MGWFBP_BLOCK) mgwfbp_stream_kernel(const Args<
             const int64_t toff = -h.first_start;
             if (!updates(KIND) || (h.flags & 1)) {
                 asm volatile("; w and v cacheable" ::: "memory");
-                fast_run<KIND, GradT, PT, NT_WV, MAXRUN>(run, A, mrg, h.layer0, toff, tile_base);
+                fast_chunk<KIND, GradT, PT, NT_WV, STEPV>(A, mrg, h.layer0, toff, tile_base, TVECS);
                 asm volatile("; end w and v cacheable" ::: "memory");
             } else {
                 asm volatile("; w and v streamed" ::: "memory");
-                fast_run<KIND, GradT, PT, true, MAXRUN>(run, A, mrg, h.layer0, toff, tile_base);
+                fast_chunk<KIND, GradT, PT, true, STEPV>(A, mrg, h.layer0, toff, tile_base, TVECS);
                 asm volatile("; end w and v streamed" ::: "memory");
             }
-            t += run;
         }
     }
 }
@@ -682,6 +549,8 @@ struct mgwfbp_ctx {
     int32_t blocks_per_cu = 0;
     int32_t xcd_contiguous = 0;
     int32_t tiles_per_wg = 0;         // 0 = per-kernel default
+    int32_t wg_per_cu = 0;            // 0 = per-kernel default, > 0 = cap, < 0 = no cap
+    int32_t step_vecs = 0;            // 0 = per-kernel default, else 1 or 2
     uint64_t resident_bytes = 0;      // budget of w + v bytes kept cacheable
     uint64_t serial = 0;              // changes whenever the tables change; never reused within a process
     // device copies
@@ -770,35 +639,75 @@ int create_common(mgwfbp_ctx** out, const uint64_t* n_elems, int32_t L, const ui
     return MGWFBP_OK;
 }
 
+// How a launch is paced (host side only).
+struct Pace {
+    size_t lds_bytes = 0;     // dynamic LDS per workgroup; unused by the kernel, it only bounds the workgroups per CU
+    int step_vecs = 1;        // vectors per lane a fast tile is walked in: 1 or 2
+};
+
 template <int KIND, typename GradT, int PT>
-int launch_one(const Args<GradT>& A, int grid, hipStream_t stream, int grid_y = 1) {
-    // the longest run of tiles a workgroup could fuse is bounded by the tiles it is given
-    if (A.tiles_per_wg >= 4 && !A.clipped)
-        hipLaunchKernelGGL((mgwfbp_stream_kernel<KIND, GradT, PT, 4>), dim3(grid, grid_y), dim3(BLOCK), 0, stream, A);
-    else if (A.tiles_per_wg >= 2 && !A.clipped)
-        hipLaunchKernelGGL((mgwfbp_stream_kernel<KIND, GradT, PT, 2>), dim3(grid, grid_y), dim3(BLOCK), 0, stream, A);
-    else
-        hipLaunchKernelGGL((mgwfbp_stream_kernel<KIND, GradT, PT, 1>), dim3(grid, grid_y), dim3(BLOCK), 0, stream, A);
+int launch_one(const Args<GradT>& A, int grid, hipStream_t stream, const Pace& pc, int grid_y = 1) {
+    bool launched = false;
+    if constexpr (TVECS % 2 == 0) {
+        if (pc.step_vecs >= 2) {
+            hipLaunchKernelGGL((mgwfbp_stream_kernel<KIND, GradT, PT, 2>), dim3(grid, grid_y), dim3(BLOCK), pc.lds_bytes,
+                               stream, A);
+            launched = true;
+        }
+    }
+    if (!launched)
+        hipLaunchKernelGGL((mgwfbp_stream_kernel<KIND, GradT, PT, 1>), dim3(grid, grid_y), dim3(BLOCK), pc.lds_bytes,
+                           stream, A);
     return note(hipGetLastError());
 }
 
 template <int KIND, typename GradT>
-int launch_by_p(const Args<GradT>& A, int grid, hipStream_t stream) {
+int launch_by_p(const Args<GradT>& A, int grid, hipStream_t stream, const Pace& pc) {
     if constexpr (KIND == K_UPDATE) {
-        return launch_one<KIND, GradT, 0>(A, grid, stream);   // no per-worker data
+        return launch_one<KIND, GradT, 0>(A, grid, stream, pc);   // no per-worker data
     } else if constexpr (KIND == K_PACK) {
         Args<GradT> B = A;                                     // P independent single-worker copies
         B.worker_split = 1;
-        return launch_one<KIND, GradT, 1>(B, grid, stream, A.P);
+        return launch_one<KIND, GradT, 1>(B, grid, stream, pc, A.P);
     } else {
         switch (A.P) {
-            case 2: return launch_one<KIND, GradT, 2>(A, grid, stream);
-            case 4: return launch_one<KIND, GradT, 4>(A, grid, stream);
-            case 8: return launch_one<KIND, GradT, 8>(A, grid, stream);
-            case 16: return launch_one<KIND, GradT, 16>(A, grid, stream);
-            default: return launch_one<KIND, GradT, 0>(A, grid, stream);
+            case 2: return launch_one<KIND, GradT, 2>(A, grid, stream, pc);
+            case 4: return launch_one<KIND, GradT, 4>(A, grid, stream, pc);
+            case 8: return launch_one<KIND, GradT, 8>(A, grid, stream, pc);
+            case 16: return launch_one<KIND, GradT, 16>(A, grid, stream, pc);
+            default: return launch_one<KIND, GradT, 0>(A, grid, stream, pc);
         }
     }
+}
+
+// Dynamic LDS per workgroup that lets exactly n workgroups share the 160 KiB of a compute unit: any total in
+// (160 KiB / (n + 1), 160 KiB / n] does; the middle of that interval keeps clear of the allocation
+// granularity, and 62 KiB keeps clear of the 64 KiB a launch may ask for without special arrangements (so
+// n = 1 is served as n = 2).  n <= 0 means no cap, and so does an n beyond what the waves of a compute unit
+// allow anyway.
+size_t lds_for_workgroups_per_cu(int32_t n) {
+    constexpr int32_t MAX_WGS = 32 * 64 / BLOCK;         // 32 waves per compute unit
+    if (n <= 0 || n >= MAX_WGS) return 0;
+    if (n < 2) n = 2;
+    constexpr size_t CU_LDS = 160u << 10;
+    constexpr size_t STATIC_LDS = sizeof(int) * (2 * MAXSEG + 1 + BLOCK / 64);
+    size_t total = (CU_LDS / static_cast<size_t>(n) + CU_LDS / static_cast<size_t>(n + 1)) / 2;
+    total = std::min<size_t>(total, 62u << 10);
+    if (total <= STATIC_LDS + 256) return 0;
+    return (total - STATIC_LDS) & ~static_cast<size_t>(255);
+}
+
+// Defaults measured with a cold memory-side cache on the DNN shapes (profiles/: pacing study).  A step of 2
+// vectors is a whole tile; the caps give a compute unit about 16 KiB (binary32) or 12 KiB (16-bit) of gradient
+// loads in flight.  Pack, whose single-worker copies have little in flight anyway, runs uncapped.
+int32_t default_step_vecs(int kind, int32_t dtype) {
+    if (TVECS % 2 != 0) return 1;
+    return (dtype == MGWFBP_BF16 && kind == K_REDUCE) ? 1 : 2;
+}
+int32_t default_workgroups_per_cu(int kind, int32_t dtype, bool long_tensors) {
+    if (kind == K_PACK) return -1;
+    if (kind == K_UPDATE) return long_tensors ? 3 : -1;   // a model of tiny tensors updates fastest uncapped
+    return dtype == MGWFBP_F32 ? 2 : 3;
 }
 
 // Where the kernels find the tables: normally the context's own device copies.
@@ -851,21 +760,11 @@ int run(mgwfbp_ctx* c, int32_t group, const void* const* grad_ptrs, void* const*
         if (dev != c->device) return MGWFBP_EINVAL;   // tables live on the device the context was made on
     }
 
-    // tiles per workgroup: PACK runs as single-worker copies, whose tiles are small (one stream in, one
-    // out), so it takes several tiles per workgroup to keep the dispatcher from being the limit.  The other
-    // kinds take pairs of tiles (16 KiB stretches per array) when the gradients are binary32 and the tensors
-    // are long enough for most pairs to lie inside one tensor: measured 2-3 % faster on the DNN shapes and
-    // 4 % slower on a model of a thousand small tensors.
+    // tiles per workgroup: PACK runs as single-worker copies, whose tiles are small (one array in, one out),
+    // so it takes several tiles per workgroup to keep the dispatcher from being the limit; every other kind
+    // takes one tile per workgroup (more than one only stretches the set of bytes the chip has in flight)
     int32_t tpw = c->tiles_per_wg;
-    if (tpw <= 0) {
-        if (KIND == K_PACK) {
-            tpw = std::max(1, 16384 / (TILE * (c->dtype == MGWFBP_F32 ? 4 : 2)));
-        } else {
-            const size_t n_seg = c->host.seg_layer.size();
-            const bool long_tensors = n_seg > 0 && c->host.tiles.size() / n_seg >= 32;
-            tpw = (c->dtype == MGWFBP_F32 && long_tensors) ? 2 : 1;
-        }
-    }
+    if (tpw <= 0) tpw = (KIND == K_PACK) ? std::max(1, 16384 / (TILE * (c->dtype == MGWFBP_F32 ? 4 : 2))) : 1;
     const int32_t units = (count + tpw - 1) / tpw;
     int grid = units;
     if (c->blocks_per_cu > 0 && c->n_cu > 0 && static_cast<int64_t>(c->n_cu) * c->blocks_per_cu < units)
@@ -875,6 +774,14 @@ int run(mgwfbp_ctx* c, int32_t group, const void* const* grad_ptrs, void* const*
         grid &= ~7;
         xcd = 1;
     }
+    // Pacing: how many vectors a lane moves per step and how many workgroups may share a compute unit.
+    // Together they set the loads a compute unit has in flight (step_vecs x 4 KiB x workgroups for binary32).
+    Pace pc;
+    pc.step_vecs = c->step_vecs > 0 ? c->step_vecs : default_step_vecs(KIND, c->dtype);
+    const size_t n_seg = c->host.seg_layer.size();
+    const bool long_tensors = n_seg > 0 && c->host.tiles.size() / n_seg >= 32;
+    const int32_t wgs = c->wg_per_cu != 0 ? c->wg_per_cu : default_workgroups_per_cu(KIND, c->dtype, long_tensors);
+    pc.lds_bytes = lds_for_workgroups_per_cu(wgs);
     hipStream_t stream = static_cast<hipStream_t>(stream_v);
     const float inv_p = 1.0f / static_cast<float>(c->P);
     const int32_t clip_on = (span != nullptr && span->clipped) ? 1 : 0;
@@ -886,14 +793,14 @@ int run(mgwfbp_ctx* c, int32_t group, const void* const* grad_ptrs, void* const*
                       reinterpret_cast<float* const*>(merge_bufs), reduced, w_ptrs, v_ptrs,
                       lr, mu, inv_p, c->host.L, c->P, t0, count, xcd, tpw, units, 0,
                       clip_on, clip_lo, clip_hi};
-        return launch_by_p<KIND, float>(A, grid, stream);
+        return launch_by_p<KIND, float>(A, grid, stream, pc);
     }
     Args<uint16_t> A{T.tiles, T.seg_n, T.seg_layer, T.seg_off,
                      reinterpret_cast<const uint16_t* const*>(grad_ptrs),
                      reinterpret_cast<uint16_t* const*>(merge_bufs), reduced, w_ptrs, v_ptrs,
                      lr, mu, inv_p, c->host.L, c->P, t0, count, xcd, tpw, units, 0,
                      clip_on, clip_lo, clip_hi};
-    return launch_by_p<KIND, uint16_t>(A, grid, stream);
+    return launch_by_p<KIND, uint16_t>(A, grid, stream, pc);
 }
 
 // Per device: where that GPU's copy of `scratch` lives and whose tables it holds.
@@ -973,6 +880,15 @@ int mgwfbp_ctx_set_launch(mgwfbp_ctx* c, int32_t blocks_per_cu, int32_t xcd_cont
     c->tiles_per_wg = tiles_per_workgroup <= 0 ? 0 : tiles_per_workgroup;
     c->blocks_per_cu = blocks_per_cu <= 0 ? DEFAULT_BLOCKS_PER_CU : blocks_per_cu;
     c->xcd_contiguous = xcd_contiguous ? 1 : 0;
+    return MGWFBP_OK;
+}
+
+int mgwfbp_ctx_set_pacing(mgwfbp_ctx* c, int32_t workgroups_per_cu, int32_t vectors_per_step) {
+    if (c == nullptr || workgroups_per_cu > 64 || vectors_per_step < 0 || vectors_per_step > TVECS ||
+        (vectors_per_step > 0 && TVECS % vectors_per_step != 0))
+        return MGWFBP_EINVAL;
+    c->wg_per_cu = workgroups_per_cu;
+    c->step_vecs = vectors_per_step;
     return MGWFBP_OK;
 }
 
