@@ -519,6 +519,9 @@ def main() -> int:
                     help="instead of the benchmark, run the bench aid's bare stream pattern with R read-only, W "
                          "write-only and X updated arrays of 512 MiB each `--steps` times (reference dispatches "
                          "for counter studies)")
+    ap.add_argument("--probe-paced", default="", metavar="LANES,VECTORS,LDS_KIB",
+                    help="with --probe-mix: walk the arrays one at a time in workgroups of LANES lanes and VECTORS "
+                         "vectors per lane, with LDS_KIB KiB of unused LDS per workgroup as occupancy cap")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (the path is per-GPU; nothing is sharded or "
@@ -554,17 +557,26 @@ def main() -> int:
         tensors = [[torch.zeros(n, dtype=torch.float32, device="cuda") for _ in range(c)] for c in mix]
         ptrs = [[t.data_ptr() for t in group] for group in tensors]
         stream = int(torch.cuda.current_stream().cuda_stream)
-        A.stream_probe(ptrs[0], ptrs[1], ptrs[2], n, stream)
+        if args.probe_paced:
+            lanes, vecs, kib = [int(x) for x in args.probe_paced.split(",")]
+
+            def probe():
+                A.paced_probe(ptrs[0], ptrs[1], ptrs[2], n, lanes, vecs, kib << 10, stream)
+        else:
+            def probe():
+                A.stream_probe(ptrs[0], ptrs[1], ptrs[2], n, stream)
+        probe()
         torch.cuda.synchronize()
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         e0.record()
         for _ in range(args.steps):
-            A.stream_probe(ptrs[0], ptrs[1], ptrs[2], n, stream)
+            probe()
         e1.record()
         torch.cuda.synchronize()
         ms = e0.elapsed_time(e1) / args.steps
         nbytes = 4 * n * (mix[0] + mix[1] + 2 * mix[2])
-        print(json.dumps({"probe_mix": mix, "bytes_per_launch": nbytes, "launches": args.steps + 1,
+        print(json.dumps({"probe_mix": mix, "paced": args.probe_paced or None, "bytes_per_launch": nbytes,
+                          "launches": args.steps + 1,
                           "ms_per_launch": round(ms, 4), "GBps": round(nbytes / ms / 1e6, 1)}))
         return 0
 

@@ -29,6 +29,9 @@ def lib() -> C.CDLL:
         h.bench_aid_stream_probe.restype = C.c_int
         h.bench_aid_stream_probe.argtypes = [C.POINTER(_vp), C.c_int32, C.POINTER(_vp), C.c_int32, C.POINTER(_vp),
                                              C.c_int32, C.c_uint64, _vp]
+        h.bench_aid_paced_probe.restype = C.c_int
+        h.bench_aid_paced_probe.argtypes = [C.POINTER(_vp), C.c_int32, C.POINTER(_vp), C.c_int32, C.POINTER(_vp),
+                                            C.c_int32, C.c_uint64, C.c_int32, C.c_int32, C.c_uint32, _vp]
         h.bench_aid_cache_scrub.restype = C.c_int
         h.bench_aid_cache_scrub.argtypes = [_vp, C.c_uint64, _vp]
         _LIB = h
@@ -44,6 +47,18 @@ def stream_probe(read_ptrs: Sequence[int], write_ptrs: Sequence[int], update_ptr
                                       table(update_ptrs), len(update_ptrs), int(elems), _vp(stream))
     if rc != 0:
         raise BenchAidError(f"bench_aid_stream_probe failed: {rc}")
+
+
+def paced_probe(read_ptrs: Sequence[int], write_ptrs: Sequence[int], update_ptrs: Sequence[int], elems: int,
+                block_lanes: int, vectors_per_step: int, lds_bytes: int, stream: int = 0) -> None:
+    """bench_aid_paced_probe: the same arrays, one array at a time, with an occupancy cap through unused LDS."""
+    def table(addrs):
+        return (_vp * max(len(addrs), 1))(*[int(a) for a in addrs]) if addrs else None
+    rc = lib().bench_aid_paced_probe(table(read_ptrs), len(read_ptrs), table(write_ptrs), len(write_ptrs),
+                                     table(update_ptrs), len(update_ptrs), int(elems), int(block_lanes),
+                                     int(vectors_per_step), int(lds_bytes), _vp(stream))
+    if rc != 0:
+        raise BenchAidError(f"bench_aid_paced_probe failed: {rc}")
 
 
 def cache_scrub(buf: int, nbytes: int, stream: int = 0) -> None:

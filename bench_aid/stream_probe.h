@@ -29,6 +29,17 @@ int bench_aid_stream_probe(const float* const* read_ptrs, int32_t n_read, float*
                            int32_t n_write, float* const* update_ptrs, int32_t n_update, uint64_t elems,
                            void* hip_stream);
 
+/* The same arrays walked one array at a time (the order the library's kernels use): a workgroup of `block_lanes`
+ * lanes owns vectors_per_step x block_lanes x 4 consecutive elements, loads its part of read array i, stores it to
+ * write array i (i < n_write; write arrays beyond n_read get 1.0f), adds it to a running sum, goes on to array
+ * i + 1, and finally adds the sum to the update arrays one after the other.  `lds_bytes` (<= 64 KiB) of unused
+ * dynamic LDS per workgroup bounds how many workgroups share a compute unit (160 KiB each), i.e. how many bytes
+ * of loads a compute unit has in flight.  (block_lanes, vectors_per_step) in {(64,1), (128,1), (128,2), (256,1),
+ * (256,2), (256,4)}; elems a multiple of vectors_per_step x block_lanes x 4; any counts 0..16, not all zero. */
+int bench_aid_paced_probe(const float* const* read_ptrs, int32_t n_read, float* const* write_ptrs,
+                          int32_t n_write, float* const* update_ptrs, int32_t n_update, uint64_t elems,
+                          int32_t block_lanes, int32_t vectors_per_step, uint32_t lds_bytes, void* hip_stream);
+
 /* Displaces whatever the memory-side cache (256 MB on MI355X) holds: copies the first half of the device
  * buffer `buf` (`bytes` long, a multiple of 8192, 16-byte aligned) onto its second half with ordinary,
  * cacheable loads and stores, so bytes/2 are read and bytes/2 are written.  With bytes >= 1 GiB nothing that

@@ -18,20 +18,23 @@
 // same 16-byte (8-byte for bfloat16) memory instructions.
 //
 // A tile that lies entirely inside one tensor takes the fast path: tensor index and source offset
-// come from the tile header, the pointer table is read once with wave-uniform addresses, and each
-// lane issues all of its loads (P gradient vectors + w + v, for every vector of the tile) before the
-// first store.  Any other tile takes the general path: the tile-local start offsets of the
-// segments it intersects are produced by a workgroup-wide prefix sum (wavefront scans via
-// cross-lane shifts, combined through LDS) over the segment lengths, staged in LDS, and each lane
-// finds the owner of its vector by binary search there.  Vectors that straddle two tensors or the
-// end of the group fall back to element-wise accesses.
+// come from the tile header, the pointer table is read once with wave-uniform addresses, and the tile is
+// walked in paced steps, one worker at a time (see paced_step).  Any other tile takes the general path:
+// the tile-local start offsets of the segments it intersects are produced by a workgroup-wide prefix sum
+// (wavefront scans via cross-lane shifts, combined through LDS) over the segment lengths, staged in LDS,
+// and each lane finds the owner of its vector by binary search there.  Vectors that straddle two tensors
+// or the end of the group fall back to element-wise accesses.
 //
-// This is bandwidth-bound streaming work (at most 4 flops per 12+ bytes), so there is no use for
-// the matrix cores; the job is to keep enough 16-byte requests in flight on every compute unit and to
-// present them to the memory system in a friendly order:
-//   - gradients, merge arenas and the reduced arena are touched once per iteration and are streamed
-//     (non-temporal loads / stores); a leading share of the weights and momenta, which come back next
-//     iteration, uses ordinary accesses so that it stays in the 256 MB memory-side cache (tile flag);
+// This is bandwidth-bound streaming work (at most 4 flops per 12+ bytes), so there is no use for the
+// matrix cores; the job is to present the traffic to the memory system in the form it serves fastest:
+//   - PACING.  For these read/write mixes MI355X delivers most when every compute unit keeps about
+//     16-24 KiB of loads in flight and a tenth less beyond that, so a lane has at most two 16-byte loads
+//     outstanding (one worker's share of the tile) and each launch asks for enough unused LDS that only
+//     2-3 workgroups share a compute unit (see run() and lds_for_workgroups_per_cu());
+//   - one workgroup per tile, dispatched in tile order, so that the bytes the chip has in flight form one
+//     contiguous moving window per array;
+//   - everything is streamed with non-temporal loads and stores; a caller may ask for a leading share of
+//     the weights and momenta to use ordinary accesses and stay in the 256 MB memory-side cache (tile flag);
 //   - PACK, which has no arithmetic across workers, runs as P single-worker copies (gridDim.y = P),
 //     so the chip streams 2 arrays at a time instead of 2P.
 //
@@ -196,9 +199,10 @@ template <typename T> struct WorkerPtrs<T, 0> {
 // (kinds that fill the arenas), add them to the running sums -- acc = g_0, then acc = acc + g_w, the worker
 // order 0..P-1 of Eq. 2 -- and go on to the next worker; then the reduced arena, then v, then w.  A lane never
 // has more than N loads in flight (kinds without stores between the workers take MGWFBP_READ_GROUP workers at a
-// time), and that is the point: the memory system serves this traffic fastest when each compute unit keeps only
-// about 16 KiB of loads in flight, and collapses by a tenth beyond about 20 KiB.  N x 4 KiB per workgroup times
-// the workgroups a compute unit is allowed to hold (see run()) sets that budget.
+// time), and that is the point: the memory system serves this traffic fastest when each compute unit keeps
+// only 16-24 KiB of loads in flight (the exact figure differs a little from one machine to the next) and about
+// a tenth slower beyond.  N x 4 KiB per workgroup times the workgroups a compute unit is allowed to hold (see
+// run()) sets that budget.
 #ifndef MGWFBP_READ_GROUP
 #define MGWFBP_READ_GROUP 2
 #endif

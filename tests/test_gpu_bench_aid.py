@@ -39,6 +39,37 @@ def test_stream_probe_moves_what_it_says(mix):
         assert np.array_equal(dev[2][j].cpu().numpy(), host[2][j] + s)
 
 
+@pytest.mark.parametrize("mix,shape", [((8, 8, 2), (256, 2, 60)), ((3, 2, 1), (128, 1, 20)), ((2, 4, 0), (64, 1, 0)),
+                                       ((0, 0, 2), (256, 4, 0)), ((5, 0, 0), (256, 1, 36)), ((1, 1, 0), (128, 2, 8))])
+def test_paced_probe_moves_what_it_says(mix, shape):
+    import torch
+    import bench_aid as A
+    r, w, x = mix
+    lanes, vecs, kib = shape
+    n = 3 * lanes * vecs * 4
+    rng = np.random.default_rng(r * 100 + w * 10 + x)
+    host = [[rng.standard_normal(n).astype(np.float32) for _ in range(c)] for c in mix]
+    dev = [[torch.from_numpy(a).cuda() for a in group] for group in host]
+    _say(f"[paced probe] mix={mix} shape={shape} n={n}")
+    A.paced_probe(*[[t.data_ptr() for t in group] for group in dev], n, lanes, vecs, kib << 10,
+                  int(torch.cuda.current_stream().cuda_stream))
+    torch.cuda.synchronize()
+    s = np.zeros(n, np.float32)
+    for a in host[0]:
+        s = s + a                                      # binary32, in array order, as the kernel adds
+    for i in range(r):
+        assert np.array_equal(dev[0][i].cpu().numpy(), host[0][i]), "inputs must not change"
+    for i in range(w):
+        want = host[0][i] if i < r else np.ones(n, np.float32)
+        assert np.array_equal(dev[1][i].cpu().numpy(), want)
+    for j in range(x):
+        assert np.array_equal(dev[2][j].cpu().numpy(), host[2][j] + s)
+    t = dev[0][0] if r else dev[2][0]
+    for bad in ((n + 4, lanes, vecs, 0), (n, 100, vecs, 0), (n, lanes, 3, 0), (n, lanes, vecs, 100 << 10)):
+        with pytest.raises(A.BenchAidError):
+            A.paced_probe([t.data_ptr()], [], [], *bad)
+
+
 def test_stream_probe_rejects_what_it_cannot_run():
     import torch
     import bench_aid as A
