@@ -404,7 +404,7 @@ def measure_workload(name, args, scrub, headline: bool):
     g = p.elem_bytes
     merged, first, plan_us, plan_us_binding = time_plan(p)
     G = int(first.shape[0])
-    ctx = M.Context(n, merged, p.P, M.BF16 if p.grad_dtype == "bf16" else M.F32)
+    ctx = M.Context(n, merged, p.P, {"f32": M.F32, "bf16": M.BF16, "f16": M.F16}[p.grad_dtype])
     if args.resident_mib >= 0:
         ctx.set_resident_bytes(args.resident_mib << 20)
     dm = H.DeviceModel(ctx, n)
@@ -450,7 +450,7 @@ def measure_workload(name, args, scrub, headline: bool):
     gbps = step_bytes / (cold_ms * 1e-3) / 1e9
     res = {
         "workload": name, "tensors": p.L, "elements": E, "groups": G, "P": p.P,
-        "dtype": "f32" if g == 4 else "bf16 gradients, f32 accumulate/update",
+        "dtype": "f32" if g == 4 else "%s gradients, f32 accumulate/update" % p.grad_dtype,
         "mode": mode, "launches_per_step": nl, "bytes_per_element": bpe, "bytes_per_step": step_bytes,
         "tile_elems": ctx.tile_elems, "tiles_per_workgroup": tpw or "default", "workgroups_per_cu": wgs,
         "vectors_per_step": args.vectors_per_step or "default", "autotune_cold_ms": tuned,

@@ -37,7 +37,7 @@
  *   - Arithmetic is binary32 with one rounding per operation (no fused multiply-add):
  *       r = ((..((g_0 + g_1) + g_2)..) + g_{P-1}) * (1.0f / P)
  *       t1 = mu * v ; v' = t1 + r ; t2 = eta * v' ; w' = w - t2
- *     bfloat16 gradients are widened exactly to binary32 before the first addition.
+ *     bfloat16 and binary16 gradients are widened exactly to binary32 before the first addition.
  *   - A context is used by one host thread at a time (its launch settings are plain fields); different
  *     contexts are independent, and the host-only functions are re-entrant.
  *   - Every function returns MGWFBP_OK (0) or a negative mgwfbp_status.  Nothing throws or aborts.
@@ -62,8 +62,10 @@ typedef enum mgwfbp_status {
 
 typedef enum mgwfbp_dtype {
     MGWFBP_F32 = 0, /* gradients are binary32, 4 bytes per element            */
-    MGWFBP_BF16 = 1 /* gradients are bfloat16 bit patterns, 2 bytes per element (Sec. 5.3:
-                       BytesPerElement = 2 for half-precision training)         */
+    MGWFBP_BF16 = 1, /* gradients are bfloat16 bit patterns, 2 bytes per element (Sec. 5.3:
+                        BytesPerElement = 2 for half-precision training)        */
+    MGWFBP_F16 = 2   /* gradients are IEEE binary16, 2 bytes per element: the half precision of the
+                        paper's own mixed-precision runs (Sec. 5.3, Sec. 6.3)   */
 } mgwfbp_dtype;
 
 typedef struct mgwfbp_ctx mgwfbp_ctx; /* opaque; host + device copies of the group/offset tables */

@@ -11,9 +11,10 @@ What each function states:
   reduce_average  Eq. 2: (1/N) * sum over workers g = 1..N of the gradients.  The sum runs in worker
                   order 0, 1, ..., P-1 in binary32; the factor is one multiply by float32(1/P)
                   (the paper fixes neither order nor placement; this is the reading both sides use).
-                  Half-precision gradients (Sec. 5.3, BytesPerElement = 2) are bfloat16 bit patterns
-                  here; they widen exactly to binary32 before the first add and the result stays
-                  binary32.
+                  Half-precision gradients (Sec. 5.3, BytesPerElement = 2) are IEEE binary16 values
+                  (numpy float16, the paper's FP16) or bfloat16 bit patterns (uint16, the benchmark
+                  configuration's); both widen exactly to binary32 before the first add and the result
+                  stays binary32.
   unpack_update   Eq. 2 / Algorithm 2 line 15 with a momentum buffer (the paper's update is plain
                   SGD; the momentum term comes from the benchmark configuration):
                       v <- mu * v + g ;  w <- w - eta * v      (four roundings, no FMA)
@@ -38,12 +39,20 @@ def widen_bf16(bits: np.ndarray) -> np.ndarray:
     return (bits.astype(np.uint32) << np.uint32(16)).view(np.float32)
 
 
+def widen_f16(x: np.ndarray) -> np.ndarray:
+    """IEEE binary16 values -> the same values in binary32 (exact: binary32 has more exponent and more
+    fraction bits)."""
+    return x.astype(np.float32)
+
+
 def as_f32(x: np.ndarray) -> np.ndarray:
     if x.dtype == np.float32:
         return x
     if x.dtype == np.uint16:
         return widen_bf16(x)
-    raise TypeError(f"gradient dtype {x.dtype} not understood (float32 or uint16 bfloat16 bits)")
+    if x.dtype == np.float16:
+        return widen_f16(x)
+    raise TypeError(f"gradient dtype {x.dtype} not understood (float32, float16 or uint16 bfloat16 bits)")
 
 
 # ------------------------------------------------------------------------------------------

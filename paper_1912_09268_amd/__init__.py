@@ -6,5 +6,5 @@ loudly if the library has not been built (run `python -m paper_1912_09268_amd.bu
 from .binding import (  # noqa: F401
     AR_BINARY_TREE, AR_DOUBLE_BINARY_TREES, AR_HALVING_DOUBLING, AR_RECURSIVE_DOUBLING, AR_RING, allreduce_ab,
     fit_ab, group_ready_times, simulate,
-    BF16, F32, Context, MgwfbpError, eval_plan, lib, library_path, plan, plan_opt,
+    BF16, F16, F32, Context, MgwfbpError, eval_plan, lib, library_path, plan, plan_opt,
 )

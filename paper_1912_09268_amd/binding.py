@@ -12,6 +12,7 @@ import numpy as np
 
 F32 = 0
 BF16 = 1
+F16 = 2
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB: Optional[C.CDLL] = None

@@ -90,22 +90,28 @@ constexpr bool needs_owner(int k) { return k != K_REDUCE; }
 // vector types that promise only element alignment
 // ---------------------------------------------------------------------------------------------
 typedef float f32x4 __attribute__((ext_vector_type(4), aligned(4)));
-typedef uint16_t u16x4 __attribute__((ext_vector_type(4), aligned(2)));
+typedef uint16_t u16x4 __attribute__((ext_vector_type(4), aligned(2)));   // bfloat16 bit patterns
+typedef _Float16 f16x4 __attribute__((ext_vector_type(4), aligned(2)));   // IEEE binary16
 
 template <typename T, int W> struct VecOf;
 template <> struct VecOf<float, 4> { typedef f32x4 type; };
 template <> struct VecOf<float, 1> { typedef float type; };
 template <> struct VecOf<uint16_t, 4> { typedef u16x4 type; };
 template <> struct VecOf<uint16_t, 1> { typedef uint16_t type; };
+template <> struct VecOf<_Float16, 4> { typedef f16x4 type; };
+template <> struct VecOf<_Float16, 1> { typedef _Float16 type; };
 
 template <typename V> struct Lanes { static constexpr int n = 4; };
 template <> struct Lanes<float> { static constexpr int n = 1; };
 template <> struct Lanes<uint16_t> { static constexpr int n = 1; };
+template <> struct Lanes<_Float16> { static constexpr int n = 1; };
 
 __device__ __forceinline__ float comp(const f32x4& v, int c) { return v[c]; }
 __device__ __forceinline__ float comp(const float& v, int) { return v; }
 __device__ __forceinline__ uint16_t comp(const u16x4& v, int c) { return v[c]; }
 __device__ __forceinline__ uint16_t comp(const uint16_t& v, int) { return v; }
+__device__ __forceinline__ _Float16 comp(const f16x4& v, int c) { return v[c]; }
+__device__ __forceinline__ _Float16 comp(const _Float16& v, int) { return v; }
 __device__ __forceinline__ void setc(f32x4& v, int c, float x) { v[c] = x; }
 __device__ __forceinline__ void setc(float& v, int, float x) { v = x; }
 
@@ -137,6 +143,7 @@ constexpr bool NT_WV = (MGWFBP_NT & 4) != 0;
 
 __device__ __forceinline__ float widen(float x) { return x; }
 __device__ __forceinline__ float widen(uint16_t bits) { return __uint_as_float(static_cast<uint32_t>(bits) << 16); }
+__device__ __forceinline__ float widen(_Float16 x) { return static_cast<float>(x); }   // every binary16 value is a binary32 value
 
 // ---------------------------------------------------------------------------------------------
 // kernel arguments
@@ -608,7 +615,7 @@ int create_common(mgwfbp_ctx** out, const uint64_t* n_elems, int32_t L, const ui
     if (out == nullptr) return MGWFBP_EINVAL;
     *out = nullptr;
     if (P < 1 || P > MGWFBP_MAX_P) return MGWFBP_EINVAL;
-    if (dtype != MGWFBP_F32 && dtype != MGWFBP_BF16) return MGWFBP_EINVAL;
+    if (dtype != MGWFBP_F32 && dtype != MGWFBP_BF16 && dtype != MGWFBP_F16) return MGWFBP_EINVAL;
     mgwfbp_ctx* c = new (std::nothrow) mgwfbp_ctx();
     if (c == nullptr) return MGWFBP_ENOMEM;
     int rc = mgwfbp_build_tables(n_elems, L, merged, c->host);
@@ -706,7 +713,7 @@ size_t lds_for_workgroups_per_cu(int32_t n) {
 // loads in flight.  Pack, whose single-worker copies have little in flight anyway, runs uncapped.
 int32_t default_step_vecs(int kind, int32_t dtype) {
     if (TVECS % 2 != 0) return 1;
-    return (dtype == MGWFBP_BF16 && kind == K_REDUCE) ? 1 : 2;
+    return (dtype != MGWFBP_F32 && kind == K_REDUCE) ? 1 : 2;
 }
 int32_t default_workgroups_per_cu(int kind, int32_t dtype, bool long_tensors) {
     if (kind == K_PACK) return -1;
@@ -798,6 +805,14 @@ int run(mgwfbp_ctx* c, int32_t group, const void* const* grad_ptrs, void* const*
                       lr, mu, inv_p, c->host.L, c->P, t0, count, xcd, tpw, units, 0,
                       clip_on, clip_lo, clip_hi};
         return launch_by_p<KIND, float>(A, grid, stream, pc);
+    }
+    if (c->dtype == MGWFBP_F16) {
+        Args<_Float16> A{T.tiles, T.seg_n, T.seg_layer, T.seg_off,
+                         reinterpret_cast<const _Float16* const*>(grad_ptrs),
+                         reinterpret_cast<_Float16* const*>(merge_bufs), reduced, w_ptrs, v_ptrs,
+                         lr, mu, inv_p, c->host.L, c->P, t0, count, xcd, tpw, units, 0,
+                         clip_on, clip_lo, clip_hi};
+        return launch_by_p<KIND, _Float16>(A, grid, stream, pc);
     }
     Args<uint16_t> A{T.tiles, T.seg_n, T.seg_layer, T.seg_off,
                      reinterpret_cast<const uint16_t* const*>(grad_ptrs),

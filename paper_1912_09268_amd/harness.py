@@ -16,11 +16,11 @@ SENTINEL16 = 0x7FC1
 
 
 def _torch_dtype(grad_dtype: int):
-    return torch.float32 if grad_dtype == B.F32 else torch.int16   # bf16 travels as raw 16-bit patterns
+    return torch.float32 if grad_dtype == B.F32 else torch.int16   # 16-bit gradients travel as raw bit patterns
 
 
 def _np_view_for_upload(a: np.ndarray) -> np.ndarray:
-    return a.view(np.int16) if a.dtype == np.uint16 else a
+    return a.view(np.int16) if a.dtype in (np.uint16, np.float16) else a
 
 
 class DeviceModel:
@@ -124,7 +124,9 @@ class DeviceModel:
 
     def download_merge(self, worker: int) -> np.ndarray:
         a = self.merge[worker].cpu().numpy()
-        return a.view(np.uint16) if a.dtype == np.int16 else a
+        if a.dtype == np.int16:
+            return a.view(np.float16) if self.ctx.grad_dtype == B.F16 else a.view(np.uint16)
+        return a
 
     def download_reduced(self) -> np.ndarray:
         return self.reduced.cpu().numpy()

@@ -98,7 +98,8 @@ def _run_mode(dm, mode, lr, mu, G):
         raise KeyError(mode)
 
 
-def check_case(profile, merged, mode, misalign=0, steps=1, seed=W.BASE_SEED, label="", launch=None, resident=None):
+def check_case(profile, merged, mode, misalign=0, steps=1, seed=W.BASE_SEED, label="", launch=None, resident=None,
+               pacing=None):
     """Run `steps` iterations on the GPU and in the oracle from the same host arrays and compare every
     output: P merge arenas, the reduced arena, weights and momenta, and the padding of the arenas."""
     import torch
@@ -109,12 +110,14 @@ def check_case(profile, merged, mode, misalign=0, steps=1, seed=W.BASE_SEED, lab
          f"{profile.grad_dtype} mode={mode} misalign={misalign} seed={seed}")
     n = [int(x) for x in profile.n_elems]
     merged = [int(x) for x in merged]
-    gdt = M.BF16 if profile.grad_dtype == "bf16" else M.F32
+    gdt = {"f32": M.F32, "bf16": M.BF16, "f16": M.F16}[profile.grad_dtype]
     ctx = M.Context(n, merged, profile.P, gdt)
     if launch is not None:
         ctx.set_launch(*launch)
     if resident is not None:
         ctx.set_resident_bytes(resident)
+    if pacing is not None:
+        ctx.set_pacing(*pacing)
     dm = H.DeviceModel(ctx, n, misalign=misalign, fill_arena=True)
     off, grp, base, ge = ctx.layout()
     groups = OP.groups_in_arrival_order(merged)
@@ -196,7 +199,7 @@ def test_toy_mlp_all_modes(mode):
 
 
 @pytest.mark.parametrize("P", [1, 2, 3, 4, 8, 16])
-@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("dtype", ["f32", "bf16", "f16"])
 def test_random_models_worker_counts(P, dtype):
     rng = np.random.default_rng(1000 + P)
     p = W.make_random_profile(rng, 50, size_hi=20000, P=P, grad_dtype=dtype, allow_empty=True)
@@ -217,7 +220,7 @@ def test_largest_worker_counts(P):
         M.Context([4, 4], [0, 1], 65, M.F32)
 
 
-@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("dtype", ["f32", "bf16", "f16"])
 @pytest.mark.parametrize("mode", ["staged", "pipeline", "direct_per_group_with_reduced"])
 def test_misaligned_sources_and_odd_sizes(dtype, mode):
     rng = np.random.default_rng(7)
@@ -298,6 +301,33 @@ def test_special_values_propagate_like_ieee():
     ctx.close()
 
 
+@pytest.mark.parametrize("dtype", ["f16", "bf16"])
+def test_every_sixteen_bit_pattern_through_pack_and_reduce(dtype):
+    """All 65536 patterns of a 16-bit gradient format (subnormals, both zeros, infinities, quiet and signalling
+    NaNs) go through pack bit for bit, and through reduce as the values the format defines."""
+    import torch
+    import paper_1912_09268_amd as M
+    from paper_1912_09268_amd import harness as H
+    n = [65536]
+    ctx = M.Context(n, [0], 2, M.F16 if dtype == "f16" else M.BF16)
+    dm = H.DeviceModel(ctx, n, fill_arena=True)
+    patterns = np.arange(65536, dtype=np.uint16)
+    g0 = patterns.view(np.float16) if dtype == "f16" else patterns
+    half = np.float16(0.5) if dtype == "f16" else np.uint16(0x3F00)
+    g1 = np.full(65536, half, dtype=g0.dtype)
+    _say(f"[parity] all 65536 {dtype} patterns, P=2")
+    dm.upload_grads(0, g0); dm.upload_grads(1, g1)
+    dm.upload_weights(np.zeros(65536, np.float32), np.zeros(65536, np.float32))
+    dm.pack(); dm.reduce()
+    torch.cuda.synchronize()
+    assert np.array_equal(_bits(dm.download_merge(0)[:65536]), patterns)
+    r = OD.reduce_average([g0, g1])
+    dev = dm.download_reduced()[:65536]
+    nan = np.isnan(r)
+    assert np.array_equal(np.isnan(dev), nan) and np.array_equal(_bits(dev)[~nan], _bits(r)[~nan])
+    ctx.close()
+
+
 def test_device_entry_points_reject_bad_arguments():
     import paper_1912_09268_amd as M
     from paper_1912_09268_amd import harness as H
@@ -339,6 +369,31 @@ def test_results_do_not_depend_on_launch_shape(launch):
         check_case(p, merged, mode, launch=launch, resident=resident, label=f"launch={launch}")
 
 
+@pytest.mark.parametrize("pacing", [(-1, 1), (-1, 2), (2, 1), (2, 2), (3, 0), (5, 2), (7, 1), (1, 0), (64, 0)])
+def test_results_do_not_depend_on_pacing(pacing):
+    """The cap on workgroups per compute unit (an amount of unused LDS per launch) and the vectors a lane moves
+    per step change when bytes move, never which bytes or what is computed from them."""
+    rng = np.random.default_rng(78)
+    p = W.make_random_profile(rng, 50, size_lo=1, size_hi=40000, P=8, allow_empty=True)
+    merged = [0] + [int(x) for x in (rng.random(p.L - 1) < 0.5)]
+    q = W.make_random_profile(rng, 20, size_lo=1, size_hi=30000, P=3, grad_dtype="bf16")
+    merged_q = [0] + [int(x) for x in (rng.random(q.L - 1) < 0.5)]
+    for mode in ("pipeline", "staged", "reduce_update", "direct"):
+        check_case(p, merged, mode, pacing=pacing, label=f"pacing={pacing}")
+    check_case(q, merged_q, "pipeline", pacing=pacing, misalign=3, label=f"pacing={pacing} bf16")
+
+
+def test_pacing_arguments_are_checked():
+    import paper_1912_09268_amd as M
+    ctx = M.Context([100, 100], [0, 1], 2, M.F32, host_only=True)
+    for bad in ((65, 0), (2, -1), (2, 3), (0, 5)):
+        with pytest.raises(M.MgwfbpError):
+            ctx.set_pacing(*bad)
+    ctx.set_pacing(0, 0)
+    ctx.set_pacing(-5, 2)
+    ctx.close()
+
+
 # ------------------------------------------------------------------------------------------
 # the benchmark configurations at full size, in the launch configuration bench.py times
 # ------------------------------------------------------------------------------------------
@@ -355,13 +410,13 @@ def test_full_size_profiles(name, mode):
     check_case(p, _plan_of(p), mode, steps=1)
 
 
-@pytest.mark.parametrize("name,tiles_per_wg", [("resnet50", 1), ("resnet50", 2), ("resnet50", 4),
-                                               ("vgg16", 1), ("vgg16", 2), ("vgg16", 4)])
-def test_full_size_in_the_benchmarks_own_launch_configuration(name, tiles_per_wg):
-    """bench.py times the fused pipeline without the optional reduced arena and with the tiles-per-workgroup
-    value its tuning step picks among 1, 2 and 4 (usually 1 on the ResNet-50 shape, 2 on the VGG-16 shape)."""
+@pytest.mark.parametrize("name,wgs", [("resnet50", 0), ("resnet50", 2), ("resnet50", 3), ("resnet50", 4),
+                                      ("vgg16", 0), ("vgg16", 2), ("vgg16", 3), ("vgg16", 4)])
+def test_full_size_in_the_benchmarks_own_launch_configuration(name, wgs):
+    """bench.py times the fused pipeline without the optional reduced arena and with the cap on workgroups per
+    compute unit that its tuning step picks among the library default (0), 2, 3 and 4."""
     p = W.make_profile(name)
-    check_case(p, _plan_of(p), "pipeline_no_reduced", steps=1, launch=(0, False, tiles_per_wg))
+    check_case(p, _plan_of(p), "pipeline_no_reduced", steps=1, pacing=(wgs, 0))
 
 
 # ------------------------------------------------------------------------------------------
@@ -375,7 +430,7 @@ def _check_incremental(profile, merged, splitter, misalign=0, label=""):
     _say(f"[incremental] {label or profile.name} L={profile.L} E={profile.total_elems} P={profile.P} {profile.grad_dtype}")
     n = [int(x) for x in profile.n_elems]
     merged = [int(x) for x in merged]
-    ctx = M.Context(n, merged, profile.P, M.BF16 if profile.grad_dtype == "bf16" else M.F32)
+    ctx = M.Context(n, merged, profile.P, {"f32": M.F32, "bf16": M.BF16, "f16": M.F16}[profile.grad_dtype])
     dm = H.DeviceModel(ctx, n, misalign=misalign, fill_arena=True)
     off, grp, base, ge = ctx.layout()
     flats = [W.worker_gradient_flat(profile, w) for w in range(profile.P)]
@@ -428,7 +483,7 @@ def _check_incremental(profile, merged, splitter, misalign=0, label=""):
     ctx.close()
 
 
-@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("dtype", ["f32", "bf16", "f16"])
 def test_pack_tensor_by_tensor_as_gradients_arrive(dtype):
     rng = np.random.default_rng(31)
     p = W.make_random_profile(rng, 70, size_lo=1, size_hi=12000, P=4, grad_dtype=dtype, allow_empty=True)
@@ -634,7 +689,7 @@ def test_many_random_models(block):
         L = int(rng.integers(1, 90))
         hi = int(rng.choice([8, 300, 3000, 30000]))
         P = int(rng.choice([1, 2, 3, 4, 5, 8, 16]))
-        dtype = str(rng.choice(["f32", "bf16"]))
+        dtype = str(rng.choice(["f32", "bf16", "f16"]))
         p = W.make_random_profile(rng, L, size_lo=1, size_hi=hi, P=P, grad_dtype=dtype, allow_empty=bool(rng.integers(0, 2)))
         merged = [0] + [int(x) for x in (rng.random(L - 1) < rng.choice([0.1, 0.5, 0.9]))]
         mode = str(rng.choice(["staged", "staged_per_group", "reduce_update", "pipeline", "pipeline_per_group",

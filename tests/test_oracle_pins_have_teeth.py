@@ -23,6 +23,8 @@ PLAN_PINS = [TP.test_small_message_example_from_introduction, TP.test_hand_timel
              TP.test_plan_optimal_equals_exhaustive_minimum,
              TP.test_plan_optimal_on_hand_example_and_wide_ranges]
 DATA_PINS = [TD.test_widen_bf16_known_patterns_and_against_torch, TD.test_reduce_bf16_inputs_accumulate_in_binary32,
+             TD.test_widen_f16_against_the_definition_of_binary16_for_every_pattern,
+             TD.test_reduce_f16_inputs_accumulate_in_binary32,
              TD.test_pack_worked_example, TD.test_pack_round_trip_and_buffer_size, TD.test_reduce_order_is_left_to_right,
              TD.test_reduce_small_integers_are_exact, TD.test_reduce_identical_copies_returns_input,
              TD.test_reduce_replayed_in_binary64_with_explicit_rounding, TD.test_reduce_non_power_of_two_uses_reciprocal_multiply,
@@ -101,6 +103,8 @@ DATA_MUTANTS = [
     ("sgd_momentum", "v[...] = np.add(t1, g, dtype=np.float32)", "v[...] = np.add(t1, np.multiply(g, eta), dtype=np.float32)"),
     ("sgd_momentum", "t2 = np.multiply(v, eta, dtype=np.float32)", "t2 = np.multiply(g, eta, dtype=np.float32)"),
     ("widen_bf16", "<< np.uint32(16)", "<< np.uint32(15)"),
+    ("widen_f16", "x.astype(np.float32)", "x.view(np.uint16).astype(np.float32)"),
+    ("as_f32", "return widen_f16(x)", "return widen_bf16(x.view(np.uint16))"),
     ("pack_as_gradients_arrive", "if merged[l - 1] == 0:", "if merged[l - 1] == 1 or l == 1:"),
 ]
 

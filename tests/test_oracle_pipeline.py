@@ -29,6 +29,43 @@ def test_widen_bf16_known_patterns_and_against_torch():
     assert np.array_equal(OD.widen_bf16(allbits).view(np.uint32), ref.view(np.uint32))
 
 
+def test_widen_f16_against_the_definition_of_binary16_for_every_pattern():
+    """Pin: IEEE 754 binary16 is sign (1 bit), exponent (5 bits, bias 15), fraction (10 bits): a normal number is
+    (-1)^s 2^(e-15) (1 + f/1024), a subnormal (e = 0) is (-1)^s 2^(-14) (f/1024), e = 31 is infinity (f = 0) or NaN.
+    Every one of the 65536 patterns is evaluated by that formula in binary64 (exact) and compared with the
+    oracle's widening; torch's own half -> float conversion is the second, independent witness."""
+    allbits = np.arange(65536, dtype=np.uint16)
+    got = OD.widen_f16(allbits.view(np.float16))
+    assert got.dtype == np.float32
+    s = (allbits >> 15).astype(np.float64)
+    e = ((allbits >> 10) & 0x1F).astype(np.int64)
+    f = (allbits & 0x3FF).astype(np.float64)
+    want = np.where(e == 0, 2.0 ** -14 * (f / 1024.0), 2.0 ** (e - 15).astype(np.float64) * (1.0 + f / 1024.0))
+    want = np.where(s == 1, -want, want)
+    finite = e != 31
+    assert np.array_equal(got[finite].astype(np.float64), want[finite])
+    assert np.array_equal(np.signbit(got[finite]), s[finite] == 1)            # also for the two zeros
+    inf = (e == 31) & (f == 0)
+    assert np.all(np.isinf(got[inf])) and np.array_equal(np.signbit(got[inf]), s[inf] == 1)
+    assert np.all(np.isnan(got[(e == 31) & (f != 0)]))
+    ref = torch.from_numpy(allbits.view(np.int16).copy()).view(torch.float16).float().numpy()
+    ok = ~np.isnan(ref)
+    assert np.array_equal(got[ok].view(np.uint32), ref[ok].view(np.uint32)) and np.array_equal(np.isnan(got), np.isnan(ref))
+    assert got[0x3C00] == 1.0 and got[0xC000] == -2.0 and got[0x0001] == 2.0 ** -24 and got[0x7BFF] == 65504.0
+
+
+def test_reduce_f16_inputs_accumulate_in_binary32():
+    """0.1 is not a binary16 number; three copies of its binary16 neighbour sum, in binary32, to a value that
+    binary16 arithmetic could not hold, and the 1/3 factor is applied in binary32."""
+    x = np.float16(0.1)
+    bufs = [np.full(5, x, np.float16) for _ in range(3)]
+    got = OD.reduce_average(bufs)
+    v = np.float32(x)
+    want = np.float32(np.float32(np.float32(v + v) + v) * (np.float32(1.0) / np.float32(3.0)))
+    assert got.dtype == np.float32 and np.all(got == want)
+    assert np.float16(np.float16(x + x) + x) != np.float32(np.float32(v + v) + v)      # binary16 adds would differ
+
+
 def test_f32_to_bf16_bits_is_round_to_nearest_even():
     rng = np.random.default_rng(0)
     x = rng.standard_normal(200_000).astype(np.float32) * np.float32(1e-3)

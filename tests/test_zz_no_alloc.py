@@ -24,7 +24,7 @@ def _both_ways(profile, merged, seed, repeats=1):
     import paper_1912_09268_amd as M
     from paper_1912_09268_amd import harness as H
     n = [int(x) for x in profile.n_elems]
-    gdt = M.BF16 if profile.grad_dtype == "bf16" else M.F32
+    gdt = {"f32": M.F32, "bf16": M.BF16, "f16": M.F16}[profile.grad_dtype]
     ctx_dev = M.Context(n, merged, profile.P, gdt)
     ctx_host = M.Context(n, merged, profile.P, gdt, host_only=True)
     ref = H.DeviceModel(ctx_dev, n, fill_arena=True)

@@ -36,7 +36,7 @@ class Profile:
     a: float                     # all-reduce startup time, seconds          (Eq. 10)
     b: float                     # all-reduce time per byte, seconds / byte  (Eq. 10)
     P: int                       # number of simulated workers
-    grad_dtype: str              # "f32" or "bf16"
+    grad_dtype: str              # "f32", "bf16" or "f16"
     grad_sigma: float            # std-dev of the gradient draw
     lr: float = 0.1
     momentum: float = 0.9
@@ -271,12 +271,15 @@ def f32_to_bf16_bits(x: np.ndarray) -> np.ndarray:
 def worker_gradient_flat(profile: Profile, worker: int, seed: int = BASE_SEED) -> np.ndarray:
     """All gradients of one simulated worker, concatenated in forward order i = 0..L-1.
 
-    float32 array for "f32" profiles, uint16 bfloat16 bit patterns for "bf16" profiles."""
+    float32 array for "f32" profiles, uint16 bfloat16 bit patterns for "bf16" profiles, float16 array
+    (IEEE binary16, rounded to nearest even from the float32 draw) for "f16" profiles."""
     rng = np.random.default_rng(seed + 1 + worker)
     g = rng.standard_normal(profile.total_elems, dtype=np.float32)
     g *= np.float32(profile.grad_sigma)
     if profile.grad_dtype == "bf16":
         return f32_to_bf16_bits(g)
+    if profile.grad_dtype == "f16":
+        return g.astype(np.float16)
     return g
 
 
