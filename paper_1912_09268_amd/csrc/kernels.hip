@@ -22,8 +22,9 @@
 // walked in paced steps, one worker at a time (see paced_step).  Any other tile takes the general path:
 // the tile-local start offsets of the segments it intersects are produced by a workgroup-wide prefix sum
 // (wavefront scans via cross-lane shifts, combined through LDS) over the segment lengths, staged in LDS,
-// and each lane finds the owner of its vector by binary search there.  Vectors that straddle two tensors
-// or the end of the group fall back to element-wise accesses.
+// and each lane finds the owner of its vector by binary search there.  Vectors that straddle two tensors,
+// the end of the group or the edge of the interval a call is clipped to are taken element by element,
+// one element per lane, after the whole vectors.
 //
 // This is bandwidth-bound streaming work (at most 4 flops per 12+ bytes), so there is no use for the
 // matrix cores; the job is to present the traffic to the memory system in the form it serves fastest:
@@ -213,6 +214,9 @@ template <typename T> struct WorkerPtrs<T, 0> {
 #ifndef MGWFBP_READ_GROUP
 #define MGWFBP_READ_GROUP 2
 #endif
+#ifndef MGWFBP_GENERAL_GROUP
+#define MGWFBP_GENERAL_GROUP 64   // workers whose loads the general path issues together (64: all of them)
+#endif
 
 // keeps the compiler from moving the next group's loads above this group's arithmetic
 __device__ __forceinline__ void pace() { __builtin_amdgcn_sched_barrier(0); }
@@ -225,11 +229,20 @@ __device__ __forceinline__ void paced_step(const Args<GradT>& A, const WorkerPtr
     typedef typename VecOf<float, W>::type FV;
     constexpr int C = Lanes<GV>::n;
     FV acc[N];
+    // the general path wants everything under way at once: its v and w loads go out before the gradients'
+    constexpr int NE = (updates(KIND) && TOGETHER) ? N : 1;
+    FV v_early[NE], w_early[NE];
+    if constexpr (updates(KIND) && TOGETHER) {
+#pragma unroll
+        for (int i = 0; i < N; ++i) v_early[i] = ld<WVNT, FV>(vp + soff + i * stride);
+#pragma unroll
+        for (int i = 0; i < N; ++i) w_early[i] = ld<WVNT, FV>(wp + soff + i * stride);
+    }
     if constexpr (reads_grads(KIND) || reads_merge(KIND)) {
         // workers whose loads are issued together: one (kinds that store each worker's share before the next
         // load), MGWFBP_READ_GROUP (kinds that only read them), or all of them / four at a time (TOGETHER: the
         // general path, whose lanes also have to fetch their own pointers and gain from overlapping all of that)
-        constexpr int GW = TOGETHER ? (PT > 0 ? PT : 4) : (writes_merge(KIND) ? 1 : MGWFBP_READ_GROUP);
+        constexpr int GW = TOGETHER ? (PT > 0 ? (PT < MGWFBP_GENERAL_GROUP ? PT : MGWFBP_GENERAL_GROUP) : 4) : (writes_merge(KIND) ? 1 : MGWFBP_READ_GROUP);
         auto some_workers = [&](int w0, int count) {      // workers w0 .. w0 + count - 1, count <= GW
             GV g[GW][N];
 #pragma unroll
@@ -242,6 +255,10 @@ __device__ __forceinline__ void paced_step(const Args<GradT>& A, const WorkerPtr
                     for (int i = 0; i < N; ++i) g[j][i] = ld<NT_LD, GV>(from + i * stride);
                 }
             }
+            // kinds that store and add each worker's share: every load of the step is issued before the first
+            // value is used (left alone, the scheduler now and then puts an add, and with it a wait for the
+            // first load, in front of the second load)
+            if constexpr (writes_merge(KIND) && sums(KIND)) pace();
 #pragma unroll
             for (int j = 0; j < GW; ++j) {
                 if (j < count) {
@@ -291,7 +308,20 @@ __device__ __forceinline__ void paced_step(const Args<GradT>& A, const WorkerPtr
             for (int i = 0; i < N; ++i) st<NT_ST, FV>(A.reduced + apos + i * stride, acc[i]);
         }
     }
-    if constexpr (updates(KIND)) {
+    if constexpr (updates(KIND) && TOGETHER) {
+#pragma unroll
+        for (int i = 0; i < N; ++i) {
+#pragma unroll
+            for (int c = 0; c < C; ++c) {
+                const float t1 = A.mu * comp(v_early[i], c);
+                setc(v_early[i], c, t1 + comp(acc[i], c));
+                const float t2 = A.lr * comp(v_early[i], c);
+                setc(w_early[i], c, comp(w_early[i], c) - t2);
+            }
+            st<WVNT, FV>(vp + soff + i * stride, v_early[i]);
+            st<WVNT, FV>(wp + soff + i * stride, w_early[i]);
+        }
+    } else if constexpr (updates(KIND)) {
         FV v[N];
 #pragma unroll
         for (int i = 0; i < N; ++i) v[i] = ld<WVNT, FV>(vp + soff + i * stride);
@@ -304,7 +334,7 @@ __device__ __forceinline__ void paced_step(const Args<GradT>& A, const WorkerPtr
             }
             st<WVNT, FV>(vp + soff + i * stride, v[i]);
         }
-        if constexpr (!TOGETHER) pace();
+        pace();
         FV w[N];
 #pragma unroll
         for (int i = 0; i < N; ++i) w[i] = ld<WVNT, FV>(wp + soff + i * stride);
@@ -387,66 +417,77 @@ __device__ __forceinline__ int block_inclusive_scan(int x, int* s_wave) {
 
 template <int KIND, typename GradT, int PT>
 __device__ void general_tile(const Args<GradT>& A, const WorkerPtrs<GradT, PT>& mrg, const TileHdr& h,
-                             int64_t tile_base, int clo, int chi, int* s_loc, int* s_layer, int* s_wave) {
+                             int64_t tile_base, int clo, int chi, int* s_loc, int* s_layer, int* s_wave,
+                             int* s_ragged, int* s_nragged) {
     // Only tile-local elements [clo, chi) are touched; 0 <= clo < chi <= h.valid.
+    //
+    // A lane takes the 4-element vectors it owns whole where it can.  A vector that is not wanted whole (it
+    // crosses a tensor boundary, the end of the group or a clip edge) is set aside in LDS, and once every whole
+    // vector is under way the elements of those vectors are dealt out one per lane: a tile pays for its ragged
+    // spots with one more step, not with up to four dependent ones in a row on a single lane while the
+    // rest of the workgroup waits.
     const int tid = threadIdx.x;
     const int valid = h.valid;
+    const int nseg = h.nseg;
     const int p_first = (clo & ~(VEC - 1)) + tid * VEC;
-    if constexpr (!needs_owner(KIND)) {
-        for (int p = p_first; p < chi; p += BLOCK * VEC) {
-            if (p >= clo && p + VEC <= chi) {
-                do_one<KIND, GradT, PT, VEC>(A, mrg, 0, 0, tile_base + p);
-            } else {
-                const int q_end = min(p + VEC, chi);
-                for (int q = max(p, clo); q < q_end; ++q) do_one<KIND, GradT, PT, 1>(A, mrg, 0, 0, tile_base + q);
-            }
+    const bool staged = needs_owner(KIND) && nseg <= MAXSEG;     // uniform over the workgroup
+    __syncthreads();                            // the previous tile's readers are done with LDS
+    if (tid == 0) *s_nragged = 0;
+    if (staged) {
+        // Tile-local start of segment j (1 <= j < nseg) = first_end + sum of the lengths of the
+        // segments 1..j-1, all of which lie wholly inside the tile.  Each lane owns entries
+        // j = 1 + 2*tid and j = 2 + 2*tid.
+        const int j0 = 1 + 2 * tid, j1 = j0 + 1;
+        int x0 = 0, x1 = 0;
+        if (j0 < nseg) x0 = (j0 == 1) ? h.first_end : static_cast<int>(ro(A.seg_n)[h.seg0 + j0 - 1]);
+        if (j1 < nseg) x1 = static_cast<int>(ro(A.seg_n)[h.seg0 + j1 - 1]);
+        const int incl = block_inclusive_scan(x0 + x1, s_wave);
+        if (j0 < nseg) s_loc[j0] = incl - x1;
+        if (j1 < nseg) s_loc[j1] = incl;
+        for (int j = tid; j < nseg; j += BLOCK) s_layer[j] = ro(A.seg_layer)[h.seg0 + j];
+        if (tid == 0) s_loc[nseg] = valid;
+    }
+    __syncthreads();
+    auto start_of = [&](int j) -> int {         // j >= 1
+        return staged ? s_loc[j] : static_cast<int>(static_cast<int64_t>(ro(A.seg_off)[h.seg0 + j]) - tile_base);
+    };
+    auto end_of = [&](int j) -> int { return (j + 1 < nseg) ? start_of(j + 1) : valid; };
+    auto layer_of = [&](int j) -> int { return staged ? s_layer[j] : ro(A.seg_layer)[h.seg0 + j]; };
+    auto owner_of = [&](int q) -> int {         // last j with start_of(j) <= q (segment 0 starts <= 0)
+        int lo = 0, hi = nseg - 1;
+        while (lo < hi) {
+            const int mid = (lo + hi + 1) >> 1;
+            if (start_of(mid) <= q) lo = mid; else hi = mid - 1;
         }
-        return;
-    } else {
-        const int nseg = h.nseg;
-        const bool staged = nseg <= MAXSEG;     // uniform over the workgroup
-        if (staged) {
-            __syncthreads();                    // the previous tile's readers are done with LDS
-            // Tile-local start of segment j (1 <= j < nseg) = first_end + sum of the lengths of the
-            // segments 1..j-1, all of which lie wholly inside the tile.  Each lane owns entries
-            // j = 1 + 2*tid and j = 2 + 2*tid.
-            const int j0 = 1 + 2 * tid, j1 = j0 + 1;
-            int x0 = 0, x1 = 0;
-            if (j0 < nseg) x0 = (j0 == 1) ? h.first_end : static_cast<int>(ro(A.seg_n)[h.seg0 + j0 - 1]);
-            if (j1 < nseg) x1 = static_cast<int>(ro(A.seg_n)[h.seg0 + j1 - 1]);
-            const int incl = block_inclusive_scan(x0 + x1, s_wave);
-            if (j0 < nseg) s_loc[j0] = incl - x1;
-            if (j1 < nseg) s_loc[j1] = incl;
-            for (int j = tid; j < nseg; j += BLOCK) s_layer[j] = ro(A.seg_layer)[h.seg0 + j];
-            if (tid == 0) s_loc[nseg] = valid;
-            __syncthreads();
+        return lo;
+    };
+    auto offset_in = [&](int j, int q) -> int64_t {   // element q of the tile is this element of segment j
+        return (j == 0) ? (static_cast<int64_t>(q) - h.first_start) : static_cast<int64_t>(q - start_of(j));
+    };
+    for (int p = p_first; p < chi; p += BLOCK * VEC) {
+        bool whole = p >= clo && p + VEC <= chi;
+        int j = 0;
+        if constexpr (needs_owner(KIND)) {
+            j = owner_of(max(p, clo));
+            whole = whole && p + VEC <= end_of(j);
         }
-        auto start_of = [&](int j) -> int {     // j >= 1
-            return staged ? s_loc[j] : static_cast<int>(static_cast<int64_t>(ro(A.seg_off)[h.seg0 + j]) - tile_base);
-        };
-        auto end_of = [&](int j) -> int { return (j + 1 < nseg) ? start_of(j + 1) : valid; };
-        auto layer_of = [&](int j) -> int { return staged ? s_layer[j] : ro(A.seg_layer)[h.seg0 + j]; };
-        for (int p = p_first; p < chi; p += BLOCK * VEC) {
-            const int q0 = max(p, clo);         // first element of this vector that is wanted
-            int lo = 0, hi = nseg - 1;          // its owner: last j with start_of(j) <= q0 (segment 0 starts <= 0)
-            while (lo < hi) {
-                const int mid = (lo + hi + 1) >> 1;
-                if (start_of(mid) <= q0) lo = mid; else hi = mid - 1;
-            }
-            int j = lo;
-            if (p >= clo && p + VEC <= min(end_of(j), chi)) {
-                const int64_t soff = (j == 0) ? (static_cast<int64_t>(p) - h.first_start)
-                                              : static_cast<int64_t>(p - start_of(j));
-                do_one<KIND, GradT, PT, VEC>(A, mrg, layer_of(j), soff, tile_base + p);
-            } else {
-                const int q_end = min(p + VEC, chi);
-                for (int q = q0; q < q_end; ++q) {
-                    while (j + 1 < nseg && q >= start_of(j + 1)) ++j;
-                    const int64_t soff = (j == 0) ? (static_cast<int64_t>(q) - h.first_start)
-                                                  : static_cast<int64_t>(q - start_of(j));
-                    do_one<KIND, GradT, PT, 1>(A, mrg, layer_of(j), soff, tile_base + q);
-                }
-            }
+        if (whole) {
+            if constexpr (needs_owner(KIND)) do_one<KIND, GradT, PT, VEC>(A, mrg, layer_of(j), offset_in(j, p), tile_base + p);
+            else do_one<KIND, GradT, PT, VEC>(A, mrg, 0, 0, tile_base + p);
+        } else {
+            s_ragged[atomicAdd(s_nragged, 1)] = p;      // at most TILE / VEC entries: one per vector of the tile
+        }
+    }
+    __syncthreads();
+    const int n_ragged = *s_nragged;
+    for (int e = tid; e < n_ragged * VEC; e += BLOCK) {
+        const int q = s_ragged[e / VEC] + (e % VEC);
+        if (q < clo || q >= chi) continue;
+        if constexpr (needs_owner(KIND)) {
+            const int j = owner_of(q);
+            do_one<KIND, GradT, PT, 1>(A, mrg, layer_of(j), offset_in(j, q), tile_base + q);
+        } else {
+            do_one<KIND, GradT, PT, 1>(A, mrg, 0, 0, tile_base + q);
         }
     }
 }
@@ -478,6 +519,8 @@ __global__ void __launch_bounds__(MGWFBP_BLOCK) mgwfbp_stream_kernel(const Args<
     __shared__ int s_loc[MAXSEG + 1];
     __shared__ int s_layer[MAXSEG];
     __shared__ int s_wave[BLOCK / 64];
+    __shared__ int s_ragged[TILE / VEC];
+    __shared__ int s_nragged;
 
     WorkerPtrs<GradT, PT> mrg;
     if constexpr (reads_merge(KIND) || writes_merge(KIND)) mrg.fetch(A.merge_bufs, 1, 0, worker_base(A));
@@ -513,7 +556,7 @@ __global__ void __launch_bounds__(MGWFBP_BLOCK) mgwfbp_stream_kernel(const Args<
                 if (chi <= clo) continue;
             }
             if (!(clo == 0 && chi == TILE && (!needs_owner(KIND) || h.nseg == 1))) {
-                general_tile<KIND, GradT, PT>(A, mrg, h, tile_base, clo, chi, s_loc, s_layer, s_wave);
+                general_tile<KIND, GradT, PT>(A, mrg, h, tile_base, clo, chi, s_loc, s_layer, s_wave, s_ragged, &s_nragged);
                 continue;
             }
             // A full tile inside one tensor.
@@ -701,7 +744,7 @@ size_t lds_for_workgroups_per_cu(int32_t n) {
     if (n <= 0 || n >= MAX_WGS) return 0;
     if (n < 2) n = 2;
     constexpr size_t CU_LDS = 160u << 10;
-    constexpr size_t STATIC_LDS = sizeof(int) * (2 * MAXSEG + 1 + BLOCK / 64);
+    constexpr size_t STATIC_LDS = sizeof(int) * (2 * MAXSEG + 1 + BLOCK / 64 + TILE / VEC + 1);
     size_t total = (CU_LDS / static_cast<size_t>(n) + CU_LDS / static_cast<size_t>(n + 1)) / 2;
     total = std::min<size_t>(total, 62u << 10);
     if (total <= STATIC_LDS + 256) return 0;

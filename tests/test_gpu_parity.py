@@ -328,6 +328,98 @@ def test_every_sixteen_bit_pattern_through_pack_and_reduce(dtype):
     ctx.close()
 
 
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("kind", ["pack", "reduce", "unpack_update", "reduce_update", "pipeline", "direct", "span",
+                                  "static"])
+def test_a_call_for_one_group_touches_only_that_group(kind, dtype):
+    """Groups lie end to end in the arena and share tiles with their neighbours.  A call for group k (or for a
+    run of groups) must produce the oracle's result for k and leave every other group's arena elements,
+    weights and momenta exactly as they were, whatever the offsets of its two ends inside a tile."""
+    import torch
+    import paper_1912_09268_amd as M
+    from paper_1912_09268_amd import harness as H
+
+    rng = np.random.default_rng(77)
+    # odd sizes around the tile (2048) and the vector (4); groups of one to three tensors
+    sizes = [1, 3, 2047, 2049, 5, 4096, 17, 1023, 6000, 2, 2048, 511, 7, 3000, 1025, 64]
+    merged = [0, 1, 0, 0, 1, 1, 0, 0, 1, 0, 0, 1, 0, 1, 1, 0]
+    prof = W.make_random_profile(rng, len(sizes), P=3, grad_dtype=dtype)
+    import dataclasses
+    prof = dataclasses.replace(prof, n_elems=np.asarray(sizes, np.uint64))
+    gdt = {"f32": M.F32, "bf16": M.BF16}[dtype]
+    n = [int(x) for x in sizes]
+    host_only = kind == "static"
+    ctx = M.Context(n, merged, prof.P, gdt, host_only=host_only)
+    layout_ctx = ctx
+    dm = H.DeviceModel(ctx, n, misalign=3, fill_arena=True)
+    off, grp, base, ge = layout_ctx.layout()
+    groups = OP.groups_in_arrival_order(merged)
+    G = len(groups)
+    seed = 4242
+    flats = [W.worker_gradient_flat(prof, w, seed) for w in range(prof.P)]
+    grads = [W.split_by_layer(f, prof.n_elems) for f in flats]
+    for w in range(prof.P):
+        dm.upload_grads(w, flats[w])
+    w_flat, v_flat = W.initial_weights_flat(prof, seed), W.initial_momentum_flat(prof, seed)
+
+    for k in range(G):
+        first, count = (k, min(2, G - k)) if kind == "span" else (k, 1)
+        chosen = list(range(first, first + count))
+        _say(f"[parity] one group alone: kind={kind} {dtype} groups {chosen} of {G}, base {int(base[k])}")
+        dm.upload_weights(w_flat, v_flat)
+        w_o = [x.copy() for x in W.split_by_layer(w_flat, prof.n_elems)]
+        v_o = [x.copy() for x in W.split_by_layer(v_flat, prof.n_elems)]
+        dm.fill_arenas()
+        if kind in ("reduce", "reduce_update", "unpack_update"):     # these read arenas: fill them for every group
+            dm.pack()
+            if kind == "unpack_update":
+                dm.reduce()
+        torch.cuda.synchronize()
+        merge_before = [dm.download_merge(w).copy() for w in range(prof.P)]
+        red_before = dm.download_reduced().copy()
+        if kind == "pack":
+            dm.pack(k)
+        elif kind == "reduce":
+            dm.reduce(k)
+        elif kind == "unpack_update":
+            dm.unpack_update(prof.lr, prof.momentum, k)
+        elif kind == "reduce_update":
+            dm.reduce_update(prof.lr, prof.momentum, k)
+        elif kind == "pipeline":
+            dm.group_pipeline(prof.lr, prof.momentum, k)
+        elif kind == "direct":
+            dm.direct_update(prof.lr, prof.momentum, k, write_reduced=True)
+        elif kind == "span":
+            dm.group_pipeline_span(prof.lr, prof.momentum, first, count)
+        elif kind == "static":
+            dm.group_pipeline_static(prof.lr, prof.momentum, k)
+        torch.cuda.synchronize()
+        merge_dev = [dm.download_merge(w) for w in range(prof.P)]
+        red_dev = dm.download_reduced()
+        inside = np.zeros(max(layout_ctx.arena_elems, 1), bool)
+        red_o = [None] * G
+        for g in chosen:
+            lo, hi = int(base[g]), int(base[g]) + int(ge[g])
+            inside[lo:hi] = True
+            bufs = [OD.pack(grads[w], [groups[g]])[0] for w in range(prof.P)]
+            red_o[g] = OD.reduce_average(bufs)
+            if kind in ("pack", "pipeline", "span", "static"):
+                for w in range(prof.P):
+                    assert np.array_equal(_bits(merge_dev[w][lo:hi]), _bits(bufs[w])), f"merge arena w={w} group={g}"
+            if kind in ("reduce", "pipeline", "direct", "span", "static"):
+                assert np.array_equal(_bits(red_dev[lo:hi]), _bits(red_o[g])), f"reduced group={g}"
+        for w in range(prof.P):           # every arena element outside the chosen groups is as it was
+            assert np.array_equal(_bits(merge_dev[w])[~inside], _bits(merge_before[w])[~inside]), f"merge arena w={w}"
+        assert np.array_equal(_bits(red_dev)[~inside], _bits(red_before)[~inside]), "reduced arena"
+        if kind not in ("pack", "reduce"):
+            OD.unpack_update([red_o[g] for g in chosen], [groups[g] for g in chosen], w_o, v_o, prof.lr,
+                             prof.momentum)
+        assert np.array_equal(_bits(dm.download_momenta()), _bits(np.concatenate(v_o))), "momentum"
+        assert np.array_equal(_bits(dm.download_weights()), _bits(np.concatenate(w_o))), "weights"
+        assert dm.guard_bands_intact()
+    ctx.close()
+
+
 def test_device_entry_points_reject_bad_arguments():
     import paper_1912_09268_amd as M
     from paper_1912_09268_amd import harness as H
