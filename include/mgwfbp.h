@@ -324,6 +324,9 @@ int mgwfbp_group_pipeline_span(mgwfbp_ctx* ctx, int32_t group_first, int32_t gro
  *   - Every call on one GPU shares that GPU's array: calls whose work may overlap in time (different streams
  *     without ordering, different host threads) race unless they pass the same unchanged context.
  *   - The context must stay alive and unchanged until the work has finished.
+ *   - A caller that captures the call into a HIP graph makes one ordinary call with the same context on the
+ *     same stream first: the table copy reads ordinary host memory and does not belong in a graph; the
+ *     captured calls then find the tables in place and only launch the kernel.
  * Errors: MGWFBP_ECAPACITY if the model's tables (32 bytes per tile of 2048 elements + 16 bytes per non-empty
  * tensor, each table rounded up to 256 bytes) exceed the array -- about 500 M elements; MGWFBP_EINVAL;
  * MGWFBP_EHIP. */
