@@ -226,9 +226,17 @@ int mgwfbp_ctx_set_launch(mgwfbp_ctx* ctx, int32_t blocks_per_cu, int32_t xcd_co
  * Their product is the load traffic a compute unit keeps in flight; MI355X serves the mixes of this library
  * fastest at about 16 KiB and about a tenth slower beyond 20 KiB.
  *   workgroups_per_cu  2..7 = cap; 0 = the library's default for the kind of kernel; < 0 or >= 8 = no cap
- *   vectors_per_step   1 or 2; 0 = the library's default
+ *   vectors_per_step   1 or 2; 0 = the library's default; -1 = the burst form (below) for every launch
  * Results never depend on it. */
 int mgwfbp_ctx_set_pacing(mgwfbp_ctx* ctx, int32_t workgroups_per_cu, int32_t vectors_per_step);
+
+/* Small launches.  A launch that covers too few tiles to fill the chip (one small group, as Algorithm 2's
+ * handler sends them) is bound by the latency of a tile, not by the memory system, and pacing only stretches
+ * that latency: such a launch takes the burst form, in which a lane issues every load of its tile at once and
+ * no cap on the workgroups per compute unit applies.  `max_tiles` is the largest launch (in tiles of 2048
+ * elements) that does so: 0 = none, < 0 = the library's default (256).  Ignored while vectors_per_step of
+ * mgwfbp_ctx_set_pacing is not 0.  Results never depend on it. */
+int mgwfbp_ctx_set_small_launch(mgwfbp_ctx* ctx, int32_t max_tiles);
 
 /* How many bytes of weights + momenta (8 per element, counted from the start of the arena) are accessed
  * with ordinary loads and stores so that they stay in the GPU's 256 MB memory-side cache from one

@@ -56,6 +56,7 @@ _SIGNATURES = {
     "mgwfbp_ctx_tables": (C.c_int, [_vp, _i32p, _vp, _u64p, _u32p, _i32p, _i32p]),
     "mgwfbp_ctx_set_launch": (C.c_int, [_vp, C.c_int32, C.c_int32, C.c_int32]),
     "mgwfbp_ctx_set_pacing": (C.c_int, [_vp, C.c_int32, C.c_int32]),
+    "mgwfbp_ctx_set_small_launch": (C.c_int, [_vp, C.c_int32]),
     "mgwfbp_ctx_set_resident_bytes": (C.c_int, [_vp, C.c_uint64]),
     "mgwfbp_pack": (C.c_int, [_vp, C.c_int32, _vp, _vp, _vp]),
     "mgwfbp_pack_tensors": (C.c_int, [_vp, C.c_int32, C.c_int32, _vp, _vp, _vp]),
@@ -279,6 +280,9 @@ class Context:
 
     def set_pacing(self, workgroups_per_cu: int = 0, vectors_per_step: int = 0) -> None:
         _check("mgwfbp_ctx_set_pacing", lib().mgwfbp_ctx_set_pacing(self._h, int(workgroups_per_cu), int(vectors_per_step)))
+
+    def set_small_launch(self, max_tiles: int = -1) -> None:
+        _check("mgwfbp_ctx_set_small_launch", lib().mgwfbp_ctx_set_small_launch(self._h, int(max_tiles)))
 
     def set_resident_bytes(self, nbytes: int) -> None:
         _check("mgwfbp_ctx_set_resident_bytes", lib().mgwfbp_ctx_set_resident_bytes(self._h, int(nbytes)))

@@ -28,6 +28,8 @@
 //
 // This is bandwidth-bound streaming work (at most 4 flops per 12+ bytes), so there is no use for the
 // matrix cores; the job is to present the traffic to the memory system in the form it serves fastest:
+//   - SMALL LAUNCHES (too few tiles to fill the chip: one small group) are bound by the latency of a tile,
+//     so they issue every load of a tile at once (the burst form, STEPV = 0); what follows is for the rest;
 //   - PACING.  For these read/write mixes MI355X delivers most when every compute unit keeps about
 //     16-24 KiB of loads in flight and a tenth less beyond that, so a lane has at most two 16-byte loads
 //     outstanding (one worker's share of the tile) and each launch asks for enough unused LDS that only
@@ -372,7 +374,7 @@ __device__ __forceinline__ void do_one(const Args<GradT>& A, const WorkerPtrs<Gr
 template <int KIND, typename GradT, int PT, bool WVNT, int STEPV>
 __device__ __forceinline__ void fast_chunk(const Args<GradT>& A, const WorkerPtrs<GradT, PT>& mrg,
                                            int layer, int64_t tensor_off, int64_t tile_base, int nvec) {
-    static_assert(TVECS % STEPV == 0, "a tile is a whole number of steps");
+    static_assert(STEPV == 0 || TVECS % STEPV == 0, "a tile is a whole number of steps");
     WorkerPtrs<const GradT, PT> src;
     float* wp = nullptr;
     float* vp = nullptr;
@@ -385,10 +387,19 @@ __device__ __forceinline__ void fast_chunk(const Args<GradT>& A, const WorkerPtr
     const int lane_elem = static_cast<int>(threadIdx.x) * VEC;
     const int64_t soff = tensor_off + lane_elem;    // this lane's first element: in its tensor
     const int64_t apos = tile_base + lane_elem;     //                            in the arena
-    for (int u = 0; u < nvec; u += STEPV) {
-        paced_step<KIND, GradT, PT, VEC, STEPV, WVNT>(A, src, mrg, wp, vp, soff + static_cast<int64_t>(u) * STEP,
-                                                      apos + static_cast<int64_t>(u) * STEP, STEP);
-        pace();
+    if constexpr (STEPV == 0) {
+        // burst: every load of the tile under way at once.  The form for a launch too small to fill the chip,
+        // where the time is the tile's own latency and not the memory system's throughput.
+        for (int u = 0; u < nvec; u += TVECS)
+            paced_step<KIND, GradT, PT, VEC, TVECS, WVNT, true>(A, src, mrg, wp, vp,
+                                                                soff + static_cast<int64_t>(u) * STEP,
+                                                                apos + static_cast<int64_t>(u) * STEP, STEP);
+    } else {
+        for (int u = 0; u < nvec; u += STEPV) {
+            paced_step<KIND, GradT, PT, VEC, STEPV, WVNT>(A, src, mrg, wp, vp, soff + static_cast<int64_t>(u) * STEP,
+                                                          apos + static_cast<int64_t>(u) * STEP, STEP);
+            pace();
+        }
     }
 }
 
@@ -513,7 +524,7 @@ __device__ __forceinline__ TileHdr load_header(const TileHdr* p) {
     return h;
 }
 
-// STEPV (1 or 2): vectors per lane a fast tile is walked in (see paced_step).
+// STEPV: vectors per lane a fast tile is walked in (1 or 2, see paced_step), or 0 for the burst form.
 template <int KIND, typename GradT, int PT, int STEPV>
 __global__ void __launch_bounds__(MGWFBP_BLOCK) mgwfbp_stream_kernel(const Args<GradT> A) {
     __shared__ int s_loc[MAXSEG + 1];
@@ -593,6 +604,8 @@ int mgwfbp_note_hip_result(int hip_error_code) { return note(static_cast<hipErro
 // ---------------------------------------------------------------------------------------------
 // context
 // ---------------------------------------------------------------------------------------------
+constexpr int32_t DEFAULT_BURST_TILES = 256;   // see run(): about half of what the chip holds at once under the cap
+
 struct mgwfbp_ctx {
     HostTables host;
     int32_t P = 0;
@@ -604,7 +617,8 @@ struct mgwfbp_ctx {
     int32_t xcd_contiguous = 0;
     int32_t tiles_per_wg = 0;         // 0 = per-kernel default
     int32_t wg_per_cu = 0;            // 0 = per-kernel default, > 0 = cap, < 0 = no cap
-    int32_t step_vecs = 0;            // 0 = per-kernel default, else 1 or 2
+    int32_t step_vecs = 0;            // 0 = per-kernel default, 1 or 2 = paced steps, -1 = always the burst form
+    int32_t burst_tiles = DEFAULT_BURST_TILES;   // launches of at most this many tiles take the burst form
     uint64_t resident_bytes = 0;      // budget of w + v bytes kept cacheable
     uint64_t serial = 0;              // changes whenever the tables change; never reused within a process
     // device copies
@@ -696,14 +710,19 @@ int create_common(mgwfbp_ctx** out, const uint64_t* n_elems, int32_t L, const ui
 // How a launch is paced (host side only).
 struct Pace {
     size_t lds_bytes = 0;     // dynamic LDS per workgroup; unused by the kernel, it only bounds the workgroups per CU
-    int step_vecs = 1;        // vectors per lane a fast tile is walked in: 1 or 2
+    int step_vecs = 1;        // vectors per lane a fast tile is walked in: 1 or 2; 0 = burst (all at once)
 };
 
 template <int KIND, typename GradT, int PT>
 int launch_one(const Args<GradT>& A, int grid, hipStream_t stream, const Pace& pc, int grid_y = 1) {
     bool launched = false;
+    if (pc.step_vecs <= 0) {
+        hipLaunchKernelGGL((mgwfbp_stream_kernel<KIND, GradT, PT, 0>), dim3(grid, grid_y), dim3(BLOCK), pc.lds_bytes,
+                           stream, A);
+        launched = true;
+    }
     if constexpr (TVECS % 2 == 0) {
-        if (pc.step_vecs >= 2) {
+        if (!launched && pc.step_vecs >= 2) {
             hipLaunchKernelGGL((mgwfbp_stream_kernel<KIND, GradT, PT, 2>), dim3(grid, grid_y), dim3(BLOCK), pc.lds_bytes,
                                stream, A);
             launched = true;
@@ -830,11 +849,15 @@ int run(mgwfbp_ctx* c, int32_t group, const void* const* grad_ptrs, void* const*
     }
     // Pacing: how many vectors a lane moves per step and how many workgroups may share a compute unit.
     // Together they set the loads a compute unit has in flight (step_vecs x 4 KiB x workgroups for binary32).
+    // A launch too small to fill the chip is bound by the latency of its tiles, not by the memory system: it
+    // takes the burst form (every load of a tile at once, no cap) unless the caller has fixed the pacing.
     Pace pc;
-    pc.step_vecs = c->step_vecs > 0 ? c->step_vecs : default_step_vecs(KIND, c->dtype);
+    const bool burst = c->step_vecs < 0 || (c->step_vecs == 0 && c->burst_tiles > 0 && count <= c->burst_tiles);
+    pc.step_vecs = burst ? 0 : (c->step_vecs > 0 ? c->step_vecs : default_step_vecs(KIND, c->dtype));
     const size_t n_seg = c->host.seg_layer.size();
     const bool long_tensors = n_seg > 0 && c->host.tiles.size() / n_seg >= 32;
-    const int32_t wgs = c->wg_per_cu != 0 ? c->wg_per_cu : default_workgroups_per_cu(KIND, c->dtype, long_tensors);
+    const int32_t wgs = c->wg_per_cu != 0 ? c->wg_per_cu
+                                          : (burst ? -1 : default_workgroups_per_cu(KIND, c->dtype, long_tensors));
     pc.lds_bytes = lds_for_workgroups_per_cu(wgs);
     hipStream_t stream = static_cast<hipStream_t>(stream_v);
     const float inv_p = 1.0f / static_cast<float>(c->P);
@@ -946,11 +969,17 @@ int mgwfbp_ctx_set_launch(mgwfbp_ctx* c, int32_t blocks_per_cu, int32_t xcd_cont
 }
 
 int mgwfbp_ctx_set_pacing(mgwfbp_ctx* c, int32_t workgroups_per_cu, int32_t vectors_per_step) {
-    if (c == nullptr || workgroups_per_cu > 64 || vectors_per_step < 0 || vectors_per_step > TVECS ||
+    if (c == nullptr || workgroups_per_cu > 64 || vectors_per_step < -1 || vectors_per_step > TVECS ||
         (vectors_per_step > 0 && TVECS % vectors_per_step != 0))
         return MGWFBP_EINVAL;
     c->wg_per_cu = workgroups_per_cu;
     c->step_vecs = vectors_per_step;
+    return MGWFBP_OK;
+}
+
+int mgwfbp_ctx_set_small_launch(mgwfbp_ctx* c, int32_t max_tiles) {
+    if (c == nullptr) return MGWFBP_EINVAL;
+    c->burst_tiles = max_tiles < 0 ? DEFAULT_BURST_TILES : max_tiles;
     return MGWFBP_OK;
 }
 
@@ -1137,8 +1166,13 @@ int mgwfbp_handler_replay(mgwfbp_ctx* c, const double* group_ready_s, double tim
         ++launches;
         next = upto;
     }
-    for (int32_t j = 0; j < n_streams; ++j) {     // drain every stream, also after a failed launch
-        const int rj = note(hipStreamSynchronize(static_cast<hipStream_t>(streams[j])));
+    // Drain every stream, also after a failed launch.  The handler thread has nothing else to do, so it polls
+    // (a blocking wait sleeps, and waking up costs tens of microseconds per stream) and then confirms.
+    for (int32_t j = 0; j < n_streams; ++j) {
+        hipStream_t sj = static_cast<hipStream_t>(streams[j]);
+        while (hipStreamQuery(sj) == hipErrorNotReady) {
+        }
+        const int rj = note(hipStreamSynchronize(sj));
         if (rc == MGWFBP_OK) rc = rj;
     }
     const double done = since_t0();

@@ -99,7 +99,7 @@ def _run_mode(dm, mode, lr, mu, G):
 
 
 def check_case(profile, merged, mode, misalign=0, steps=1, seed=W.BASE_SEED, label="", launch=None, resident=None,
-               pacing=None):
+               pacing=None, small_launch=None):
     """Run `steps` iterations on the GPU and in the oracle from the same host arrays and compare every
     output: P merge arenas, the reduced arena, weights and momenta, and the padding of the arenas."""
     import torch
@@ -118,6 +118,8 @@ def check_case(profile, merged, mode, misalign=0, steps=1, seed=W.BASE_SEED, lab
         ctx.set_resident_bytes(resident)
     if pacing is not None:
         ctx.set_pacing(*pacing)
+    if small_launch is not None:
+        ctx.set_small_launch(small_launch)
     dm = H.DeviceModel(ctx, n, misalign=misalign, fill_arena=True)
     off, grp, base, ge = ctx.layout()
     groups = OP.groups_in_arrival_order(merged)
@@ -461,10 +463,12 @@ def test_results_do_not_depend_on_launch_shape(launch):
         check_case(p, merged, mode, launch=launch, resident=resident, label=f"launch={launch}")
 
 
-@pytest.mark.parametrize("pacing", [(-1, 1), (-1, 2), (2, 1), (2, 2), (3, 0), (5, 2), (7, 1), (1, 0), (64, 0)])
+@pytest.mark.parametrize("pacing", [(-1, 1), (-1, 2), (2, 1), (2, 2), (3, 0), (5, 2), (7, 1), (1, 0), (64, 0),
+                                    (0, -1), (3, -1)])
 def test_results_do_not_depend_on_pacing(pacing):
     """The cap on workgroups per compute unit (an amount of unused LDS per launch) and the vectors a lane moves
-    per step change when bytes move, never which bytes or what is computed from them."""
+    per step (-1: every load of a tile at once, the form small launches take by default) change when bytes move,
+    never which bytes or what is computed from them."""
     rng = np.random.default_rng(78)
     p = W.make_random_profile(rng, 50, size_lo=1, size_hi=40000, P=8, allow_empty=True)
     merged = [0] + [int(x) for x in (rng.random(p.L - 1) < 0.5)]
@@ -478,12 +482,27 @@ def test_results_do_not_depend_on_pacing(pacing):
 def test_pacing_arguments_are_checked():
     import paper_1912_09268_amd as M
     ctx = M.Context([100, 100], [0, 1], 2, M.F32, host_only=True)
-    for bad in ((65, 0), (2, -1), (2, 3), (0, 5)):
+    for bad in ((65, 0), (2, -2), (2, 3), (0, 5)):
         with pytest.raises(M.MgwfbpError):
             ctx.set_pacing(*bad)
     ctx.set_pacing(0, 0)
     ctx.set_pacing(-5, 2)
+    ctx.set_pacing(2, -1)
+    ctx.set_small_launch(0)
+    ctx.set_small_launch(-1)
     ctx.close()
+
+
+@pytest.mark.parametrize("max_tiles", [0, 7, 1 << 30])
+def test_results_do_not_depend_on_the_small_launch_threshold(max_tiles):
+    """Launches of at most `max_tiles` tiles take the burst form, larger ones the paced form: 0 sends every
+    launch down the paced path, 7 splits the per-group launches of this model between the two, 2^30 sends all
+    of them down the burst path."""
+    rng = np.random.default_rng(79)
+    p = W.make_random_profile(rng, 40, size_lo=1, size_hi=60000, P=4, allow_empty=True)
+    merged = [0] + [int(x) for x in (rng.random(p.L - 1) < 0.4)]
+    for mode in ("pipeline", "pipeline_per_group", "staged_per_group", "direct_per_group_with_reduced"):
+        check_case(p, merged, mode, small_launch=max_tiles, label=f"small launch <= {max_tiles} tiles")
 
 
 # ------------------------------------------------------------------------------------------
