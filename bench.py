@@ -52,11 +52,11 @@ ALL_WORKLOADS = ("vgg16", "resnet50", "transformer", "tiny_layers", "toy_mlp")
 # source it was measured on: the key is the git blob hash of csrc/kernels.hip, and bench.py reports null when
 # the file has changed since.
 MEASURED_FABRIC_BYTES = {
-    "c5981ab4511a7d1efd7589e13f80affbf27e2a64": {
+    "e7d8d78b0dce599e6ca532e039526482dbbfb8cf": {
         ("vgg16", "pipeline"): 1.10773e+10,
         ("resnet50", "pipeline"): 2.04649e+09,
         ("transformer", "pipeline"): 1.61082e+10,
-        ("tiny_layers", "pipeline"): 1.87616e+09,
+        ("tiny_layers", "pipeline"): 1.87612e+09,
     },
 }
 
