@@ -207,6 +207,41 @@ def pattern_ceiling(P: int, reps: int = 8):
     return 4 * n * (mix[0] + mix[1] + 2 * mix[2]) / (ms * 1e-3) / 1e9
 
 
+def achievable_references(P: int, reps: int = 6):
+    """Two more figures of the same GPU to read the kernel against: the same P + P + 2 mix walked the way the
+    kernels walk it (one array at a time, two 16-byte vectors per lane, two workgroups per compute unit), and a
+    plain copy of one array onto another.  GB/s each (None where the aid has no instance)."""
+    import torch
+    import bench_aid as A
+    n = 64 << 20
+    stream = int(torch.cuda.current_stream().cuda_stream)
+
+    def timed(fn):
+        fn()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / reps
+
+    out = {"paced_pattern_GBps": None, "plain_copy_GBps": None}
+    if P in (1, 2, 4, 8, 16):
+        t = [[torch.zeros(n, dtype=torch.float32, device="cuda") for _ in range(c)] for c in (P, P, 2)]
+        ptrs = [[x.data_ptr() for x in g] for g in t]
+        ms = timed(lambda: A.paced_probe(ptrs[0], ptrs[1], ptrs[2], n, 256, 2, 62 << 10, stream))
+        out["paced_pattern_GBps"] = round(4 * n * (2 * P + 4) / (ms * 1e-3) / 1e9, 1)
+        del t
+    t = [[torch.zeros(2 * n, dtype=torch.float32, device="cuda")] for _ in range(2)]
+    ms = timed(lambda: A.stream_probe([t[0][0].data_ptr()], [t[1][0].data_ptr()], [], 2 * n, stream))
+    out["plain_copy_GBps"] = round(4 * 2 * n * 2 / (ms * 1e-3) / 1e9, 1)
+    del t
+    torch.cuda.empty_cache()
+    return out
+
+
 def kernel_source_hash() -> str:
     """git's blob hash of the kernel source, computed without git."""
     data = open(os.path.join(ROOT, "paper_1912_09268_amd", "csrc", "kernels.hip"), "rb").read()
@@ -587,6 +622,7 @@ def main() -> int:
         others[name], _ = measure_workload(name, args, scrub, headline=False)
 
     ceiling = None if args.no_ceiling else pattern_ceiling(head["P"])
+    refs = {} if args.no_ceiling else achievable_references(head["P"])
     nl = head["launches_per_step"]
     kernel_ms = head["ms_per_step"] / nl
     achieved = (head["bytes_per_step"] / nl) / (kernel_ms * 1e-3) / 1e9
@@ -618,7 +654,8 @@ def main() -> int:
                      "kernel_source_blob": khash,
                      "kernel": "mgwfbp_stream_kernel<%s>" % args.mode, "avg_launch_ms": round(kernel_ms, 5),
                      "algorithmic_bytes_per_launch": head["bytes_per_step"] // nl,
-                     "bare_pattern_GBps": None if ceiling is None else round(ceiling, 1)},
+                     "bare_pattern_GBps": None if ceiling is None else round(ceiling, 1),
+                     **refs},
         "target_70pct": {k: by_name[k]["frac_of_8TBps"] for k in ("resnet50", "vgg16") if k in by_name},
         "launch_forms": head.get("launch_forms"),
         "workloads": others,
