@@ -550,6 +550,10 @@ def main() -> int:
     ap.add_argument("--copy-calibration", type=float, default=0.0, metavar="GiB",
                     help="instead of the benchmark, run a plain device copy of this many GiB `--steps` times "
                          "(reference dispatch of known size for scaling rocprofv3's FETCH_SIZE / WRITE_SIZE)")
+    ap.add_argument("--small-launch-study", action="store_true",
+                    help="instead of the benchmark, time single launches of the fused pipeline over 1 .. 4096 "
+                         "tiles (one tensor, P = 8, binary32, cold cache, HIP events) in the paced and in the "
+                         "burst form: where the library's threshold for small launches comes from")
     ap.add_argument("--probe-mix", default="", metavar="R,W,X",
                     help="instead of the benchmark, run the bench aid's bare stream pattern with R read-only, W "
                          "write-only and X updated arrays of 512 MiB each `--steps` times (reference dispatches "
@@ -583,6 +587,33 @@ def main() -> int:
         print(json.dumps({"calibration": "plain device copy", "bytes_read": nbytes, "bytes_written": nbytes,
                           "launches": args.steps, "ms_per_copy": round(ms, 4),
                           "GBps": round(2 * nbytes / ms / 1e6, 1)}))
+        return 0
+
+    if args.small_launch_study:
+        import statistics
+        import paper_1912_09268_amd as M
+        from paper_1912_09268_amd import harness as H
+        scrub = Scrubber()
+        rows = []
+        for tiles in (1, 16, 64, 128, 256, 384, 512, 768, 1024, 2048, 4096):
+            ctx = M.Context([tiles * 2048], [0], 8, M.F32)
+            dm = H.DeviceModel(ctx, [tiles * 2048])
+            for w in range(8):
+                dm.grads[w][0].normal_(0.0, 1e-2)
+            dm.w[0].normal_()
+            dm.v[0].zero_()
+            row = {"tiles": tiles}
+            for form, vectors in (("paced", 0), ("burst", -1)):
+                ctx.set_small_launch(0)
+                ctx.set_pacing(0, vectors)
+                ms = time_cold(lambda: run_step(dm, "pipeline", 0.1, 0.9, 1), scrub, args.steps, args.warmup)
+                row[form + "_us"] = round(1e3 * statistics.median(ms), 2)
+            rows.append(row)
+            ctx.close()
+            del dm
+        print(json.dumps({"small_launch_study": "fused pipeline, one tensor of `tiles` x 2048 elements, P = 8, "
+                          "binary32, one launch per step, cache scrubbed before each, median of per-step HIP-event "
+                          "pairs (which include a few us of launch floor)", "steps": args.steps, "rows": rows}))
         return 0
 
     if args.probe_mix:
