@@ -435,6 +435,8 @@ def measure_workload(name, args, scrub, headline: bool):
     p = W.make_profile(name)
     if args.workers > 0:
         p = dataclasses.replace(p, P=args.workers)
+    if args.grad_dtype != "profile":
+        p = dataclasses.replace(p, grad_dtype=args.grad_dtype)
     n = [int(x) for x in p.n_elems]
     g = p.elem_bytes
     merged, first, plan_us, plan_us_binding = time_plan(p)
@@ -550,6 +552,9 @@ def main() -> int:
     ap.add_argument("--copy-calibration", type=float, default=0.0, metavar="GiB",
                     help="instead of the benchmark, run a plain device copy of this many GiB `--steps` times "
                          "(reference dispatch of known size for scaling rocprofv3's FETCH_SIZE / WRITE_SIZE)")
+    ap.add_argument("--grad-dtype", default="profile", choices=("profile", "f32", "bf16", "f16"),
+                    help="gradient type of every workload: the profile's own, or binary32 / bfloat16 / IEEE binary16 "
+                         "(the half precision of the paper's mixed-precision runs)")
     ap.add_argument("--small-launch-study", action="store_true",
                     help="instead of the benchmark, time single launches of the fused pipeline over 1 .. 4096 "
                          "tiles (one tensor, P = 8, binary32, cold cache, HIP events) in the paced and in the "
@@ -658,7 +663,8 @@ def main() -> int:
     kernel_ms = head["ms_per_step"] / nl
     achieved = (head["bytes_per_step"] / nl) / (kernel_ms * 1e-3) / 1e9
     khash = kernel_source_hash()
-    traffic = MEASURED_FABRIC_BYTES.get(khash, {}).get((args.workload, args.mode)) if args.workers == 0 else None
+    as_measured = args.workers == 0 and args.grad_dtype == "profile"      # the stored figures are for the profiles as they are
+    traffic = MEASURED_FABRIC_BYTES.get(khash, {}).get((args.workload, args.mode)) if as_measured else None
     by_name = dict(others)
     by_name[args.workload] = head
     out = {
