@@ -809,3 +809,33 @@ def test_many_random_models(block):
         check_case(p, merged, mode, misalign=int(rng.choice([0, 0, 3, 5])), launch=launch,
                    resident=int(rng.choice([0, 1 << 16, 1 << 30])), seed=int(rng.integers(1, 10 ** 6)),
                    label=f"random block {block} case {case}")
+
+
+def test_random_models_for_a_while():
+    """The same checker driven by a random generator over every mode, launch shape, pacing and small-launch
+    setting, for MGWFBP_RANDOM_SECONDS seconds (default 5) from seed MGWFBP_RANDOM_SEED (default 31337); set the
+    two variables to sweep longer or elsewhere."""
+    import os
+    budget = float(os.environ.get("MGWFBP_RANDOM_SECONDS", "5"))
+    seed0 = int(os.environ.get("MGWFBP_RANDOM_SEED", "31337"))
+    rng = np.random.default_rng(seed0)
+    t0 = time.time()
+    cases = 0
+    while cases == 0 or time.time() - t0 < budget:
+        L = int(rng.integers(1, 120))
+        hi = int(rng.choice([8, 300, 3000, 30000, 200000]))
+        P = int(rng.choice([1, 2, 3, 4, 5, 7, 8, 16, 17]))
+        dtype = str(rng.choice(["f32", "bf16", "f16"]))
+        p = W.make_random_profile(rng, L, size_lo=1, size_hi=hi, P=P, grad_dtype=dtype,
+                                  allow_empty=bool(rng.integers(0, 2)))
+        merged = [0] + [int(x) for x in (rng.random(L - 1) < rng.choice([0.1, 0.5, 0.9]))]
+        mode = str(rng.choice(list(MODES)))
+        launch = (int(rng.choice([0, 1, 3])), bool(rng.integers(0, 2)), int(rng.choice([0, 1, 2, 5])))
+        pacing = (int(rng.choice([0, -1, 2, 3, 5])), int(rng.choice([0, 0, -1, 1, 2])))
+        check_case(p, merged, mode, misalign=int(rng.choice([0, 0, 3, 5])), launch=launch, pacing=pacing,
+                   small_launch=int(rng.choice([-1, 0, 3, 40, 1 << 30])),
+                   resident=int(rng.choice([0, 1 << 16, 1 << 30])), seed=int(rng.integers(1, 10 ** 6)),
+                   steps=int(rng.choice([1, 1, 2])), label=f"random sweep {seed0} case {cases}")
+        cases += 1
+    _say(f"[parity] random sweep from seed {seed0}: {cases} cases in {time.time() - t0:.0f} s, all bit-exact")
+
