@@ -501,7 +501,7 @@ def measure_workload(name, args, scrub, headline: bool):
     }
     if not args.no_launch_forms and mode == "pipeline" and G > 0:
         res["launch_forms"] = launch_forms(dm, p, merged, G, scrub, cold_ms, max(5, args.steps // 3))
-    if args.all_modes:
+    if args.all_modes or (headline and not args.no_other_modes):
         ctx.set_pacing(0, args.vectors_per_step)          # every other kind at the library's own pacing
         others = {}
         for m in ("pipeline", "direct", "pack", "reduce", "unpack_update", "reduce_update", "staged"):
@@ -511,6 +511,7 @@ def measure_workload(name, args, scrub, headline: bool):
                                              max(10, args.steps // 2), 2))
             b = bytes_per_element(m, p.P, g) * E
             others[m] = {"ms_per_step": round(ms, 5), "GBps": round(b / (ms * 1e-3) / 1e9, 1),
+                         "frac_of_8TBps": round(b / (ms * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),
                          "bytes_per_element": bytes_per_element(m, p.P, g), "launches_per_step": launches_per_step(m, G)}
         res["other_modes_cold"] = others
     extra = {"profile": p, "merged": merged, "flats": flats, "step_bytes": step_bytes}
@@ -533,7 +534,10 @@ def main() -> int:
                              "reduce_update", "staged", "staged_per_group"])
     ap.add_argument("--workers", type=int, default=0,
                     help="override the profile's worker count P (1 = the share one GPU of a data-parallel job holds)")
-    ap.add_argument("--all-modes", action="store_true", help="also time the other modes, cold (extra keys)")
+    ap.add_argument("--all-modes", action="store_true",
+                    help="time the other modes (pack, reduce, unpack_update, ... each alone), cold, for every workload "
+                         "and not only for the headline one")
+    ap.add_argument("--no-other-modes", action="store_true", help="skip the other modes also for the headline")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-launch-forms", action="store_true")
     ap.add_argument("--no-ceiling", action="store_true")
