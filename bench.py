@@ -209,7 +209,8 @@ def pattern_ceiling(P: int, reps: int = 8):
 
 def achievable_references(P: int, reps: int = 6):
     """Two more figures of the same GPU to read the kernel against: the same P + P + 2 mix walked the way the
-    kernels walk it (one array at a time, two 16-byte vectors per lane, two workgroups per compute unit), and a
+    kernels walk it (one array at a time, workgroups of one wavefront with one 16-byte vector per lane in flight,
+    sixteen of them per compute unit), and a
     plain copy of one array onto another.  GB/s each (None where the aid has no instance)."""
     import torch
     import bench_aid as A
@@ -231,7 +232,7 @@ def achievable_references(P: int, reps: int = 6):
     if P in (1, 2, 4, 8, 16):
         t = [[torch.zeros(n, dtype=torch.float32, device="cuda") for _ in range(c)] for c in (P, P, 2)]
         ptrs = [[x.data_ptr() for x in g] for g in t]
-        ms = timed(lambda: A.paced_probe(ptrs[0], ptrs[1], ptrs[2], n, 256, 2, 62 << 10, stream))
+        ms = timed(lambda: A.paced_probe(ptrs[0], ptrs[1], ptrs[2], n, 64, 1, 9728, stream))
         out["paced_pattern_GBps"] = round(4 * n * (2 * P + 4) / (ms * 1e-3) / 1e9, 1)
         del t
     t = [[torch.zeros(2 * n, dtype=torch.float32, device="cuda")] for _ in range(2)]
@@ -465,7 +466,7 @@ def measure_workload(name, args, scrub, headline: bool):
     tuned = None
     if args.workgroups_per_cu == "auto" and "per_group" not in mode:
         best, tuned = "default", {}
-        for k in ("default", 2, 3, 4):
+        for k in ("default", 14, 18, 22, -1):
             ctx.set_pacing(0 if k == "default" else k, args.vectors_per_step)
             tuned[str(k)] = round(statistics.median(time_cold(step, scrub, 7, 2)), 5)
             if tuned[str(k)] < tuned[str(best)] * 0.995:      # prefer the earlier on a tie
@@ -548,9 +549,11 @@ def main() -> int:
     ap.add_argument("--tiles-per-workgroup", type=int, default=0,
                     help="consecutive tiles per workgroup; 0 = library default")
     ap.add_argument("--workgroups-per-cu", default="auto",
-                    help="pacing: workgroups a compute unit may hold; 'auto' = pick among the library default, 2, 3 "
-                         "and 4 by timing a few cold steps first, 'default' = library default, n = fixed, -1 = no cap")
-    ap.add_argument("--vectors-per-step", type=int, default=0, help="pacing: 1 or 2; 0 = library default")
+                    help="pacing: workgroups (of one wavefront) a compute unit may hold; 'auto' = pick among the library "
+                         "default, 14, 18, 22 and no cap by timing a few cold steps first, 'default' = library default, "
+                         "n = fixed, -1 = no cap")
+    ap.add_argument("--vectors-per-step", type=int, default=0,
+                    help="pacing: 0 = library default, 1 = paced walk for every launch, -1 = burst form for every launch")
     ap.add_argument("--resident-mib", type=int, default=-1,
                     help="MiB of w+v kept cacheable (library default, 0, if negative)")
     ap.add_argument("--copy-calibration", type=float, default=0.0, metavar="GiB",
@@ -560,8 +563,8 @@ def main() -> int:
                     help="gradient type of every workload: the profile's own, or binary32 / bfloat16 / IEEE binary16 "
                          "(the half precision of the paper's mixed-precision runs)")
     ap.add_argument("--small-launch-study", action="store_true",
-                    help="instead of the benchmark, time single launches of the fused pipeline over 1 .. 4096 "
-                         "tiles (one tensor, P = 8, binary32, cold cache, HIP events) in the paced and in the "
+                    help="instead of the benchmark, time single launches of the fused pipeline over 2 Ki .. 8 Mi "
+                         "elements (one tensor, P = 8, binary32, cold cache, HIP events) in the paced and in the "
                          "burst form: where the library's threshold for small launches comes from")
     ap.add_argument("--probe-mix", default="", metavar="R,W,X",
                     help="instead of the benchmark, run the bench aid's bare stream pattern with R read-only, W "
@@ -604,14 +607,15 @@ def main() -> int:
         from paper_1912_09268_amd import harness as H
         scrub = Scrubber()
         rows = []
-        for tiles in (1, 16, 64, 128, 256, 384, 512, 768, 1024, 2048, 4096):
-            ctx = M.Context([tiles * 2048], [0], 8, M.F32)
-            dm = H.DeviceModel(ctx, [tiles * 2048])
+        for kelems in (2, 32, 128, 256, 512, 768, 1024, 1536, 2048, 4096, 8192):     # Ki elements in the launch
+            ctx = M.Context([kelems * 1024], [0], 8, M.F32)
+            dm = H.DeviceModel(ctx, [kelems * 1024])
+            tiles = ctx.n_tiles
             for w in range(8):
                 dm.grads[w][0].normal_(0.0, 1e-2)
             dm.w[0].normal_()
             dm.v[0].zero_()
-            row = {"tiles": tiles}
+            row = {"tiles": tiles, "elements": kelems * 1024}
             for form, vectors in (("paced", 0), ("burst", -1)):
                 ctx.set_small_launch(0)
                 ctx.set_pacing(0, vectors)
@@ -620,7 +624,7 @@ def main() -> int:
             rows.append(row)
             ctx.close()
             del dm
-        print(json.dumps({"small_launch_study": "fused pipeline, one tensor of `tiles` x 2048 elements, P = 8, "
+        print(json.dumps({"small_launch_study": "fused pipeline, one tensor of `tiles` tiles, P = 8, "
                           "binary32, one launch per step, cache scrubbed before each, median of per-step HIP-event "
                           "pairs (which include a few us of launch floor)", "steps": args.steps, "rows": rows}))
         return 0

@@ -208,8 +208,9 @@ int mgwfbp_ctx_tables(const mgwfbp_ctx* ctx, int32_t* n_segments, void* tiles_ou
                       uint64_t* seg_off_out, uint32_t* seg_n_out, int32_t* seg_layer_out,
                       int32_t* group_tile_out);
 
-/* Launch shape.  By default a call launches one workgroup of 256 lanes per tile it covers (per 16 KiB of each
- * worker's data for mgwfbp_pack, which runs as P single-worker copies).
+/* Launch shape.  A tile is 256 consecutive arena elements.  By default a call launches one workgroup of 64 lanes
+ * (one wavefront) per tile it covers (per 4 KiB of each worker's data for mgwfbp_pack, which runs as P
+ * single-worker copies).
  *   blocks_per_cu > 0        caps the grid at compute units * blocks_per_cu workgroups, which then stride
  *                            over the work; <= 0 restores the default
  *   xcd_contiguous != 0      renumbers workgroups so that each of the 8 accelerator dies walks one
@@ -220,21 +221,23 @@ int mgwfbp_ctx_tables(const mgwfbp_ctx* ctx, int32_t* n_segments, void* tiles_ou
 int mgwfbp_ctx_set_launch(mgwfbp_ctx* ctx, int32_t blocks_per_cu, int32_t xcd_contiguous,
                           int32_t tiles_per_workgroup);
 
-/* Pacing.  The kernels walk a tile in steps of `vectors_per_step` 16-byte vectors per lane, one worker at a
- * time, so that a workgroup has vectors_per_step x 4 KiB of loads in flight (half that for 16-bit gradients),
- * and a launch asks for enough (unused) LDS that at most `workgroups_per_cu` workgroups share a compute unit.
- * Their product is the load traffic a compute unit keeps in flight; MI355X serves the mixes of this library
- * fastest at about 16 KiB and about a tenth slower beyond 20 KiB.
- *   workgroups_per_cu  2..7 = cap; 0 = the library's default for the kind of kernel; < 0 or >= 8 = no cap
- *   vectors_per_step   1 or 2; 0 = the library's default; -1 = the burst form (below) for every launch
+/* Pacing.  The kernels walk a tile one worker at a time with one 16-byte load per lane in flight, so that a
+ * workgroup has 1 KiB of loads under way (half that for 16-bit gradients), and a launch asks for enough (unused)
+ * LDS that at most `workgroups_per_cu` workgroups share a compute unit.  Their product is the load traffic a
+ * compute unit keeps in flight; MI355X serves the mixes of this library fastest at about 16 KiB and about a
+ * tenth slower beyond 20 KiB.
+ *   workgroups_per_cu  2..31 = cap; 0 = the library's default for the kind of kernel; < 0 or >= 32 = no cap
+ *                      (a compute unit holds 32 wavefronts)
+ *   vectors_per_step   1 (the only paced step of a one-vector tile); 0 = the library's default; -1 = the burst
+ *                      form (below) for every launch
  * Results never depend on it. */
 int mgwfbp_ctx_set_pacing(mgwfbp_ctx* ctx, int32_t workgroups_per_cu, int32_t vectors_per_step);
 
 /* Small launches.  A launch that covers too few tiles to fill the chip (one small group, as Algorithm 2's
  * handler sends them) is bound by the latency of a tile, not by the memory system, and pacing only stretches
  * that latency: such a launch takes the burst form, in which a lane issues every load of its tile at once and
- * no cap on the workgroups per compute unit applies.  `max_tiles` is the largest launch (in tiles of 2048
- * elements) that does so: 0 = none, < 0 = the library's default (256).  Ignored while vectors_per_step of
+ * no cap on the workgroups per compute unit applies.  `max_tiles` is the largest launch (in tiles of 256
+ * elements) that does so: 0 = none, < 0 = the library's default (2048 tiles = 512 Ki elements).  Ignored while vectors_per_step of
  * mgwfbp_ctx_set_pacing is not 0.  Results never depend on it. */
 int mgwfbp_ctx_set_small_launch(mgwfbp_ctx* ctx, int32_t max_tiles);
 
@@ -335,10 +338,10 @@ int mgwfbp_group_pipeline_span(mgwfbp_ctx* ctx, int32_t group_first, int32_t gro
  *   - A caller that captures the call into a HIP graph makes one ordinary call with the same context on the
  *     same stream first: the table copy reads ordinary host memory and does not belong in a graph; the
  *     captured calls then find the tables in place and only launch the kernel.
- * Errors: MGWFBP_ECAPACITY if the model's tables (32 bytes per tile of 2048 elements + 16 bytes per non-empty
- * tensor, each table rounded up to 256 bytes) exceed the array -- about 500 M elements; MGWFBP_EINVAL;
+ * Errors: MGWFBP_ECAPACITY if the model's tables (32 bytes per tile of 256 elements + 16 bytes per non-empty
+ * tensor, each table rounded up to 256 bytes) exceed the array -- about 400 M elements; MGWFBP_EINVAL;
  * MGWFBP_EHIP. */
-#define MGWFBP_STATIC_TABLE_MAX_BYTES (8u << 20)
+#define MGWFBP_STATIC_TABLE_MAX_BYTES (48u << 20)
 int mgwfbp_group_pipeline_static(mgwfbp_ctx* ctx, int32_t group, const void* const* d_grad_ptrs,
                                  void* const* d_merge_bufs, float* d_reduced,
                                  float* const* d_w_ptrs, float* const* d_v_ptrs,

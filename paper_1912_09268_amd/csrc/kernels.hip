@@ -2,7 +2,7 @@
 // kernels pack / reduce / unpack_update and their fused forms.
 //
 // All six operations are the same walk over the merge arena, tile by tile (by default one workgroup
-// of 256 lanes = 4 wavefronts per tile, dispatched in tile order):
+// of 64 lanes = one wavefront per tile of 256 elements, dispatched in tile order):
 //
 //   kind            reads                          writes
 //   PACK            per-layer gradients (P)        merge arenas (P)                     Sec. 5.3
@@ -62,6 +62,9 @@
 #define MGWFBP_NT 3   // bit 0: non-temporal loads of gradients / merge / reduced, bit 1: non-temporal
                       // stores to merge / reduced, bit 2: non-temporal accesses to w and v
 #endif
+#ifndef MGWFBP_PACK_TILES
+#define MGWFBP_PACK_TILES 2       // consecutive full tiles of one tensor that PACK copies in one step
+#endif
 #define MGWFBP_MAXSEG (2 * MGWFBP_BLOCK)   // segments per tile whose offsets are staged in LDS (two per lane)
 
 // Table space of mgwfbp_group_pipeline_static: one copy per GPU, held until the process ends.  Host code must
@@ -78,6 +81,7 @@ constexpr int VEC = MGWFBP_VEC;
 constexpr int TVECS = MGWFBP_TILE_VECS;
 constexpr int TILE = MGWFBP_TILE_ELEMS;
 constexpr int MAXSEG = MGWFBP_MAXSEG;
+constexpr int PACK_TILES = MGWFBP_PACK_TILES;
 
 enum Kind { K_PACK = 0, K_REDUCE = 1, K_UPDATE = 2, K_REDUCE_UPDATE = 3, K_PIPELINE = 4, K_DIRECT = 5 };
 
@@ -407,7 +411,7 @@ __device__ __forceinline__ void fast_chunk(const Args<GradT>& A, const WorkerPtr
 // general path
 // ---------------------------------------------------------------------------------------------
 
-// Inclusive prefix sum across the 256 lanes of the workgroup: shift-and-add inside each wavefront,
+// Inclusive prefix sum across the lanes of the workgroup: shift-and-add inside each wavefront,
 // wavefront totals combined through LDS.  Every lane of the workgroup must call it.
 __device__ __forceinline__ int block_inclusive_scan(int x, int* s_wave) {
     const int lane = threadIdx.x & 63;
@@ -571,6 +575,27 @@ __global__ void __launch_bounds__(MGWFBP_BLOCK) mgwfbp_stream_kernel(const Args<
                 continue;
             }
             // A full tile inside one tensor.
+            if constexpr (KIND == K_PACK && PACK_TILES > 1) {
+                // Pack is a plain copy and wants more bytes in flight per lane than one tile holds: when the next
+                // tiles of this workgroup's share are full tiles of the same tensor too, they are copied together.
+                if (!A.clipped && t + PACK_TILES <= t_end) {
+                    bool same = true;
+#pragma unroll
+                    for (int k = 1; k < PACK_TILES; ++k) {
+                        const TileHdr hk = load_header(A.tiles + tile + k);
+                        same = same && hk.valid == TILE && hk.nseg == 1 && hk.layer0 == h.layer0;
+                    }
+                    if (same) {
+                        WorkerPtrs<const GradT, PT> src;
+                        src.fetch(A.grad_ptrs, A.L, h.layer0, worker_base(A));
+                        const int lane_elem = static_cast<int>(threadIdx.x) * VEC;
+                        paced_step<KIND, GradT, PT, VEC, PACK_TILES * TVECS, true>(
+                            A, src, mrg, nullptr, nullptr, -h.first_start + lane_elem, tile_base + lane_elem, BLOCK * VEC);
+                        t += PACK_TILES - 1;
+                        continue;
+                    }
+                }
+            }
             // Tiles flagged "resident" keep their w and v in the memory-side cache between iterations
             // (ordinary loads and stores); all other w, v traffic is streamed past it like the gradients.
             // The two arms differ only in the cache policy of their memory instructions; the empty asm
@@ -604,7 +629,7 @@ int mgwfbp_note_hip_result(int hip_error_code) { return note(static_cast<hipErro
 // ---------------------------------------------------------------------------------------------
 // context
 // ---------------------------------------------------------------------------------------------
-constexpr int32_t DEFAULT_BURST_TILES = 256;   // see run(): about half of what the chip holds at once under the cap
+constexpr int32_t DEFAULT_BURST_TILES = 524288 / TILE;   // see run(): launches of at most 512 Ki elements
 
 struct mgwfbp_ctx {
     HostTables host;
@@ -770,17 +795,18 @@ size_t lds_for_workgroups_per_cu(int32_t n) {
     return (total - STATIC_LDS) & ~static_cast<size_t>(255);
 }
 
-// Defaults measured with a cold memory-side cache on the DNN shapes (profiles/: pacing study).  A step of 2
-// vectors is a whole tile; the caps give a compute unit about 16 KiB (binary32) or 12 KiB (16-bit) of gradient
-// loads in flight.  Pack, whose single-worker copies have little in flight anyway, runs uncapped.
-int32_t default_step_vecs(int kind, int32_t dtype) {
-    if (TVECS % 2 != 0) return 1;
-    return (dtype != MGWFBP_F32 && kind == K_REDUCE) ? 1 : 2;
-}
+// Defaults measured with a cold memory-side cache on the DNN shapes (profiles/: pacing study).  With one
+// 16-byte load per lane in flight a wavefront has 1 KiB of a binary32 array under way (512 bytes of a 16-bit
+// one), so a cap of 16 wavefronts gives a compute unit 16 KiB; the kinds that only read between their stores,
+// and everything with 16-bit gradients, want more.
+int32_t default_step_vecs(int, int32_t) { return TVECS % 2 == 0 ? 2 : 1; }
 int32_t default_workgroups_per_cu(int kind, int32_t dtype, bool long_tensors) {
-    if (kind == K_PACK) return -1;
-    if (kind == K_UPDATE) return long_tensors ? 3 : -1;   // a model of tiny tensors updates fastest uncapped
-    return dtype == MGWFBP_F32 ? 2 : 3;
+    const bool wide = dtype == MGWFBP_F32;
+    switch (kind) {
+        case K_REDUCE: return wide ? 14 : 15;
+        case K_UPDATE: return long_tensors ? 28 : -1;    // a model of tiny tensors updates fastest uncapped
+        default: return wide ? 16 : -1;                  // pack, reduce_update, pipeline, direct
+    }
 }
 
 // Where the kernels find the tables: normally the context's own device copies.
@@ -834,10 +860,11 @@ int run(mgwfbp_ctx* c, int32_t group, const void* const* grad_ptrs, void* const*
     }
 
     // tiles per workgroup: PACK runs as single-worker copies, whose tiles are small (one array in, one out),
-    // so it takes several tiles per workgroup to keep the dispatcher from being the limit; every other kind
-    // takes one tile per workgroup (more than one only stretches the set of bytes the chip has in flight)
+    // so a workgroup takes 4 KiB of its worker's data (two tiles at a time, see the kernel); every other kind
+    // takes one tile per workgroup.  More only stretches the set of bytes the chip has in flight: the window
+    // the workgroups of a compute unit cover together should stay within a few hundred KiB per array.
     int32_t tpw = c->tiles_per_wg;
-    if (tpw <= 0) tpw = (KIND == K_PACK) ? std::max(1, 16384 / (TILE * (c->dtype == MGWFBP_F32 ? 4 : 2))) : 1;
+    if (tpw <= 0) tpw = (KIND == K_PACK) ? std::max(1, 4096 / (TILE * (c->dtype == MGWFBP_F32 ? 4 : 2))) : 1;
     const int32_t units = (count + tpw - 1) / tpw;
     int grid = units;
     if (c->blocks_per_cu > 0 && c->n_cu > 0 && static_cast<int64_t>(c->n_cu) * c->blocks_per_cu < units)

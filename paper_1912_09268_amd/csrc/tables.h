@@ -16,10 +16,10 @@
 #include <vector>
 
 #ifndef MGWFBP_TILE_VECS
-#define MGWFBP_TILE_VECS 2          // 16-byte vectors per lane per tile
+#define MGWFBP_TILE_VECS 1          // 16-byte vectors per lane per tile
 #endif
 #ifndef MGWFBP_BLOCK
-#define MGWFBP_BLOCK 256            // lanes per workgroup (a multiple of 64: wavefronts of 64)
+#define MGWFBP_BLOCK 64             // lanes per workgroup (a multiple of 64): one wavefront per tile
 #endif
 #define MGWFBP_VEC 4                // elements per lane-vector
 #define MGWFBP_TILE_ELEMS (MGWFBP_BLOCK * MGWFBP_VEC * MGWFBP_TILE_VECS)
