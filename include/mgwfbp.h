@@ -227,7 +227,8 @@ int mgwfbp_ctx_set_launch(mgwfbp_ctx* ctx, int32_t blocks_per_cu, int32_t xcd_co
  * compute unit keeps in flight; MI355X serves the mixes of this library fastest at about 16 KiB and about a
  * tenth slower beyond 20 KiB.
  *   workgroups_per_cu  2..31 = cap; 0 = the library's default for the kind of kernel; < 0 or >= 32 = no cap
- *                      (a compute unit holds 32 wavefronts)
+ *                      (a compute unit holds 32 wavefronts).  LDS is granted in blocks, so the caps that exist
+ *                      are 25, 21, 18, 16, 14, 12, 11, 10, 9, 8, ...; a value in between acts as the next lower one.
  *   vectors_per_step   1 (the only paced step of a one-vector tile); 0 = the library's default; -1 = the burst
  *                      form (below) for every launch
  * Results never depend on it. */
@@ -237,7 +238,7 @@ int mgwfbp_ctx_set_pacing(mgwfbp_ctx* ctx, int32_t workgroups_per_cu, int32_t ve
  * handler sends them) is bound by the latency of a tile, not by the memory system, and pacing only stretches
  * that latency: such a launch takes the burst form, in which a lane issues every load of its tile at once and
  * no cap on the workgroups per compute unit applies.  `max_tiles` is the largest launch (in tiles of 256
- * elements) that does so: 0 = none, < 0 = the library's default (2048 tiles = 512 Ki elements).  Ignored while vectors_per_step of
+ * elements) that does so: 0 = none, < 0 = the library's default (1024 tiles = 256 Ki elements).  Ignored while vectors_per_step of
  * mgwfbp_ctx_set_pacing is not 0.  Results never depend on it. */
 int mgwfbp_ctx_set_small_launch(mgwfbp_ctx* ctx, int32_t max_tiles);
 

@@ -15,7 +15,7 @@
 // The arena side of every access is 16-byte aligned (tiles start on multiples of the tile size and
 // lanes step in 4-element vectors).  The per-layer side starts wherever the tensor starts, so it is
 // accessed through vector types that only promise element alignment; gfx950 executes those as the
-// same 16-byte (8-byte for bfloat16) memory instructions.
+// same 16-byte (8-byte for 16-bit gradients) memory instructions.
 //
 // A tile that lies entirely inside one tensor takes the fast path: tensor index and source offset
 // come from the tile header, the pointer table is read once with wave-uniform addresses, and the tile is
@@ -31,15 +31,21 @@
 //   - SMALL LAUNCHES (too few tiles to fill the chip: one small group) are bound by the latency of a tile,
 //     so they issue every load of a tile at once (the burst form, STEPV = 0); what follows is for the rest;
 //   - PACING.  For these read/write mixes MI355X delivers most when every compute unit keeps about
-//     16-24 KiB of loads in flight and a tenth less beyond that, so a lane has at most two 16-byte loads
-//     outstanding (one worker's share of the tile) and each launch asks for enough unused LDS that only
-//     2-3 workgroups share a compute unit (see run() and lds_for_workgroups_per_cu());
+//     16-24 KiB of loads in flight and a tenth less beyond that, so a lane has one 16-byte load outstanding
+//     (one worker's share of the tile; two workers' in the kinds that only read between their stores) and each
+//     launch asks for enough unused LDS that only about 16 workgroups share a compute unit (see run() and
+//     lds_for_workgroups_per_cu());
+//   - SMALL WORKGROUPS.  A workgroup is one wavefront and a tile the 256 elements it covers with one vector per
+//     lane: the same bytes in flight spread over sixteen independent wavefronts per compute unit, each at its
+//     own point of its walk, load the memory system more evenly than two workgroups of four wavefronts that
+//     move in step (3-5 % of the peak on every shape);
 //   - one workgroup per tile, dispatched in tile order, so that the bytes the chip has in flight form one
 //     contiguous moving window per array;
 //   - everything is streamed with non-temporal loads and stores; a caller may ask for a leading share of
 //     the weights and momenta to use ordinary accesses and stay in the 256 MB memory-side cache (tile flag);
 //   - PACK, which has no arithmetic across workers, runs as P single-worker copies (gridDim.y = P),
-//     so the chip streams 2 arrays at a time instead of 2P.
+//     so the chip streams 2 arrays at a time instead of 2P; a workgroup copies 4 KiB of its worker's data,
+//     two tiles per step (more per workgroup stretches the window its compute unit covers and costs 8 %).
 //
 // Arithmetic contract: binary32, one rounding per operation.  The file must be compiled with
 // -ffp-contract=off so that mu*v + g and w - lr*v are never fused.
@@ -215,8 +221,8 @@ template <typename T> struct WorkerPtrs<T, 0> {
 // has more than N loads in flight (kinds without stores between the workers take MGWFBP_READ_GROUP workers at a
 // time), and that is the point: the memory system serves this traffic fastest when each compute unit keeps
 // only 16-24 KiB of loads in flight (the exact figure differs a little from one machine to the next) and about
-// a tenth slower beyond.  N x 4 KiB per workgroup times the workgroups a compute unit is allowed to hold (see
-// run()) sets that budget.
+// a tenth slower beyond.  N x 16 bytes per lane of the workgroup times the workgroups a compute unit is allowed
+// to hold (see run()) sets that budget.
 #ifndef MGWFBP_READ_GROUP
 #define MGWFBP_READ_GROUP 2
 #endif
@@ -629,7 +635,7 @@ int mgwfbp_note_hip_result(int hip_error_code) { return note(static_cast<hipErro
 // ---------------------------------------------------------------------------------------------
 // context
 // ---------------------------------------------------------------------------------------------
-constexpr int32_t DEFAULT_BURST_TILES = 524288 / TILE;   // see run(): launches of at most 512 Ki elements
+constexpr int32_t DEFAULT_BURST_TILES = 262144 / TILE;   // see run(): launches of at most 256 Ki elements
 
 struct mgwfbp_ctx {
     HostTables host;
@@ -778,34 +784,40 @@ int launch_by_p(const Args<GradT>& A, int grid, hipStream_t stream, const Pace& 
     }
 }
 
-// Dynamic LDS per workgroup that lets exactly n workgroups share the 160 KiB of a compute unit: any total in
-// (160 KiB / (n + 1), 160 KiB / n] does; the middle of that interval keeps clear of the allocation
-// granularity, and 62 KiB keeps clear of the 64 KiB a launch may ask for without special arrangements (so
-// n = 1 is served as n = 2).  n <= 0 means no cap, and so does an n beyond what the waves of a compute unit
-// allow anyway.
+// Dynamic LDS per workgroup that lets at most n workgroups share the 160 KiB of a compute unit.  A workgroup's
+// LDS (static + dynamic) is granted in blocks of 1280 bytes (a 128th of the compute unit's; seen in the cap
+// sweeps, where 12 and 13, 14 and 15, 16 and 17 behave alike); the total aimed at is the smallest multiple of
+// the block above 160 KiB / (n + 1), so n + 1 workgroups never fit, and n do wherever a multiple of the block
+// lies in (160 KiB / (n + 1), 160 KiB / n]: 32, 25, 21, 18, 16, 14, 12, 11, 10, 9, 8, ... are the caps that
+// exist, and a request in between gets the next lower one.  The request stays 64 bytes short of that total so
+// that padding of the static part cannot push it into the next block.  62 KiB keeps clear of the 64 KiB a launch may ask for without special arrangements (so n = 1 is
+// served as n = 2).  n <= 0 means no cap, and so does an n beyond what the waves of a compute unit allow anyway.
 size_t lds_for_workgroups_per_cu(int32_t n) {
     constexpr int32_t MAX_WGS = 32 * 64 / BLOCK;         // 32 waves per compute unit
     if (n <= 0 || n >= MAX_WGS) return 0;
     if (n < 2) n = 2;
     constexpr size_t CU_LDS = 160u << 10;
+    constexpr size_t GRAIN = 1280;
     constexpr size_t STATIC_LDS = sizeof(int) * (2 * MAXSEG + 1 + BLOCK / 64 + TILE / VEC + 1);
-    size_t total = (CU_LDS / static_cast<size_t>(n) + CU_LDS / static_cast<size_t>(n + 1)) / 2;
+    size_t total = (CU_LDS / static_cast<size_t>(n + 1) / GRAIN + 1) * GRAIN;
     total = std::min<size_t>(total, 62u << 10);
-    if (total <= STATIC_LDS + 256) return 0;
-    return (total - STATIC_LDS) & ~static_cast<size_t>(255);
+    if (total <= STATIC_LDS + 64 + GRAIN) return 0;
+    return total - STATIC_LDS - 64;
 }
 
 // Defaults measured with a cold memory-side cache on the DNN shapes (profiles/: pacing study).  With one
 // 16-byte load per lane in flight a wavefront has 1 KiB of a binary32 array under way (512 bytes of a 16-bit
-// one), so a cap of 16 wavefronts gives a compute unit 16 KiB; the kinds that only read between their stores,
-// and everything with 16-bit gradients, want more.
+// one), so a cap of 16 wavefronts gives a compute unit 16 KiB; with 16-bit gradients every wave slot is needed
+// to get there, and the update alone (20 bytes per element, nothing per worker) runs best uncapped.
 int32_t default_step_vecs(int, int32_t) { return TVECS % 2 == 0 ? 2 : 1; }
-int32_t default_workgroups_per_cu(int kind, int32_t dtype, bool long_tensors) {
+int32_t default_workgroups_per_cu(int kind, int32_t dtype) {
     const bool wide = dtype == MGWFBP_F32;
     switch (kind) {
-        case K_REDUCE: return wide ? 14 : 15;
-        case K_UPDATE: return long_tensors ? 28 : -1;    // a model of tiny tensors updates fastest uncapped
-        default: return wide ? 16 : -1;                  // pack, reduce_update, pipeline, direct
+        case K_REDUCE: return 14;
+        case K_UPDATE: return -1;
+        case K_PACK:
+        case K_REDUCE_UPDATE: return wide ? 14 : -1;
+        default: return wide ? 16 : -1;                  // pipeline, direct
     }
 }
 
@@ -881,10 +893,8 @@ int run(mgwfbp_ctx* c, int32_t group, const void* const* grad_ptrs, void* const*
     Pace pc;
     const bool burst = c->step_vecs < 0 || (c->step_vecs == 0 && c->burst_tiles > 0 && count <= c->burst_tiles);
     pc.step_vecs = burst ? 0 : (c->step_vecs > 0 ? c->step_vecs : default_step_vecs(KIND, c->dtype));
-    const size_t n_seg = c->host.seg_layer.size();
-    const bool long_tensors = n_seg > 0 && c->host.tiles.size() / n_seg >= 32;
     const int32_t wgs = c->wg_per_cu != 0 ? c->wg_per_cu
-                                          : (burst ? -1 : default_workgroups_per_cu(KIND, c->dtype, long_tensors));
+                                          : (burst ? -1 : default_workgroups_per_cu(KIND, c->dtype));
     pc.lds_bytes = lds_for_workgroups_per_cu(wgs);
     hipStream_t stream = static_cast<hipStream_t>(stream_v);
     const float inv_p = 1.0f / static_cast<float>(c->P);

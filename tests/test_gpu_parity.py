@@ -521,11 +521,12 @@ def test_full_size_profiles(name, mode):
     check_case(p, _plan_of(p), mode, steps=1)
 
 
-@pytest.mark.parametrize("name,wgs", [("resnet50", 0), ("resnet50", 14), ("resnet50", 18), ("resnet50", -1),
-                                      ("vgg16", 0), ("vgg16", 14), ("vgg16", 18), ("vgg16", -1)])
+@pytest.mark.parametrize("name,wgs", [("resnet50", 0), ("resnet50", 14), ("resnet50", 18), ("resnet50", 21),
+                                      ("resnet50", -1), ("vgg16", 0), ("vgg16", 14), ("vgg16", 18), ("vgg16", 21),
+                                      ("vgg16", -1)])
 def test_full_size_in_the_benchmarks_own_launch_configuration(name, wgs):
     """bench.py times the fused pipeline without the optional reduced arena and with the cap on workgroups per
-    compute unit that its tuning step picks among the library default (0), 2, 3 and 4."""
+    compute unit that its tuning step picks among the library default (0), 14, 18, 21 and none."""
     p = W.make_profile(name)
     check_case(p, _plan_of(p), "pipeline_no_reduced", steps=1, pacing=(wgs, 0))
 
